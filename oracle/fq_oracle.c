@@ -1,0 +1,404 @@
+/*
+ * fq_oracle.c — CPU oracle for the FlattenQuant per-tensor-quantized linear layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct statement of
+ * what the method computes, written from the paper (arXiv 2402.17985).  It is used by the
+ * tests, by the smoke check and by the benchmark's CPU-baseline leg.  The GPU library never
+ * calls it, shares no header, table or helper with it, and must not be routed through it.
+ *
+ * Every function is the definition written out as loops: no blocking, no fusion, no
+ * reordering beyond what the definition states.  The only parallelism is an OpenMP
+ * "parallel for" over independent output rows.
+ *
+ * Conventions
+ *   X   activations, M x K, row-major (K contiguous), fp32 (bf16/fp16 inputs are widened
+ *       exactly to fp32 by the caller before they reach the oracle).
+ *   W   weights in the nn.Linear storage layout, N x K row-major.  The paper writes
+ *       Y = X W with W's j-th input channel matching X's j-th channel (Sec. 4.1, Eq. 4);
+ *       "repeat weight channel j" is therefore "repeat column j of the N x K array".
+ *   k   bit width, 8 or 4.  qmax = 2^(k-1) - 1 (Eq. 1), qmin = -2^(k-1).
+ *   map src[p] (source channel of flattened slot p, -1 for padding) and rep[p] (n of that
+ *       source channel, 0 for padding), p in [0, Kpad).
+ *
+ * Parity status: every function here is pinned by tests/test_oracle_*.py against values the
+ * paper or plain arithmetic fixes (hand-worked examples, closed forms, brute force, the
+ * X'W' = XW identity).  No function is "parity unpinned".
+ *
+ * Build: gcc -O3 -fopenmp -ffp-contract=off -shared -fPIC  (see oracle/build.py)
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define FQO_OK 0
+#define FQO_ERR_ARG 1
+#define FQO_ERR_CAP 2
+#define FQO_ERR_OVERFLOW 3
+
+int fqo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int qmax_of(int bits) { return (1 << (bits - 1)) - 1; }
+static int qmin_of(int bits) { return -(1 << (bits - 1)); }
+
+/* ------------------------------------------------------------------------------------------
+ * Flatten plan.  Sec. 4.1, Eq. 2: a channel whose calibrated max |x| exceeds the threshold T
+ * receives extra channels; Eq. 3 fixes where they live: the original keeps index j, the
+ * extras of channel j sit in an appended block starting at C + sum_{k<j} E_k, channels in
+ * increasing j.  Reading taken for the count: total copies n_j = max(1, ceil(max_j / T)),
+ * E_j = n_j - 1 (equals Eq. 2's floor except when max_j is an exact multiple of T, where
+ * Eq. 2 would add one more, all-zero, channel).  The ratio is evaluated in float64.
+ * The final channel count is padded up to a multiple of `align` (Sec. 5.1, "padded to a
+ * multiple of 32"); padding slots have src = -1, rep = 0.
+ *
+ * Call with cap = 0 (src, rep may be NULL) to obtain Kprime/Kpad only.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_plan(const float *chmax, int K, float T, int align,
+             int32_t *src, int32_t *rep, int cap, int *Kprime_out, int *Kpad_out)
+{
+    if (!chmax || K <= 0 || align <= 0 || !(T > 0.0f) || isinf(T)) return FQO_ERR_ARG;
+    long long extra = 0;
+    for (int j = 0; j < K; ++j) {
+        float c = chmax[j];
+        if (!(c >= 0.0f) || isinf(c)) return FQO_ERR_ARG;   /* NaN, negative, Inf */
+        double r = (double)c / (double)T;
+        long long n = (long long)ceil(r);
+        if (n < 1) n = 1;
+        extra += n - 1;
+        if (extra > 0x3fffffff) return FQO_ERR_OVERFLOW;
+    }
+    long long Kprime = (long long)K + extra;
+    long long Kpad = (Kprime + align - 1) / align * align;
+    if (Kpad > 0x7fffffff) return FQO_ERR_OVERFLOW;
+    if (Kprime_out) *Kprime_out = (int)Kprime;
+    if (Kpad_out) *Kpad_out = (int)Kpad;
+    if (cap == 0) return FQO_OK;
+    if (!src || !rep) return FQO_ERR_ARG;
+    if (cap < Kpad) return FQO_ERR_CAP;
+
+    int next = K;                                   /* first free appended slot */
+    for (int j = 0; j < K; ++j) {
+        double r = (double)chmax[j] / (double)T;
+        int n = (int)ceil(r);
+        if (n < 1) n = 1;
+        src[j] = j;                                 /* the original keeps its index */
+        rep[j] = n;
+        for (int e = 0; e < n - 1; ++e) {           /* its E_j extras, appended in channel order */
+            src[next] = j;
+            rep[next] = n;
+            ++next;
+        }
+    }
+    for (int p = next; p < (int)Kpad; ++p) { src[p] = -1; rep[p] = 0; }
+    return FQO_OK;
+}
+
+/* max |v| over a buffer, fp32 (exact: max is order independent). */
+float fqo_absmax(const float *v, long long count)
+{
+    float a = 0.0f;
+    for (long long i = 0; i < count; ++i) {
+        float t = fabsf(v[i]);
+        if (t > a) a = t;
+    }
+    return a;
+}
+
+/* Round-half-to-even of an fp32 value to an integer, then clamp to the k-bit range.
+ * Eq. 1's "round"; reading taken: ties to even (what rintf does in the default rounding
+ * mode, and what torch.round does). */
+static int round_clamp(float v, int bits)
+{
+    float r = rintf(v);
+    int lo = qmin_of(bits), hi = qmax_of(bits);
+    if (r < (float)lo) return lo;
+    if (r > (float)hi) return hi;
+    return (int)r;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Weights, offline (Eq. 1 and Eq. 4).  s_w = max|W| / qmax.  The division by s_w is carried
+ * out as one fp32 multiply by m_w = fl32(qmax / max|W|) (quotient formed in float64, rounded
+ * once to fp32), then round-half-even, then clamp.  Column j of Wq is then repeated at every
+ * slot p with src[p] = j; padding slots hold 0.  (Quantize-then-repeat equals
+ * repeat-then-quantize because repetition does not change the maximum.)
+ * An all-zero W gives all-zero output and s_w = 1.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_flatten_weights(const float *W, int N, int K, const int32_t *src, int Kpad, int bits,
+                        int8_t *Wq_out /* N x Kpad */, float *s_w_out)
+{
+    if (!W || !src || !Wq_out || !s_w_out || N <= 0 || K <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    if (bits != 8 && bits != 4) return FQO_ERR_ARG;
+    float a_w = fqo_absmax(W, (long long)N * K);
+    int qmax = qmax_of(bits);
+    float m_w, s_w;
+    if (a_w == 0.0f) { m_w = 0.0f; s_w = 1.0f; }
+    else {
+        m_w = (float)((double)qmax / (double)a_w);
+        s_w = (float)((double)a_w / (double)qmax);
+    }
+    *s_w_out = s_w;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p];
+            int q = 0;
+            if (j >= 0) {
+                float prod = W[(size_t)n * K + j] * m_w;      /* one IEEE fp32 multiply */
+                q = round_clamp(prod, bits);
+            }
+            Wq_out[(size_t)n * Kpad + p] = (int8_t)q;
+        }
+    }
+    return FQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Dynamic per-tensor absmax of the flattened activation (Eq. 1's max|X| applied to X').
+ * With the equal split each of the n_j copies of channel j holds x/n_j, so
+ *     a' = max over slots p of  fl32( max_i |x[i, src[p]]| / (float)rep[p] ),
+ * one IEEE fp32 division per slot.
+ * ---------------------------------------------------------------------------------------- */
+float fqo_act_absmax_dynamic(const float *X, int M, int K, int ldx,
+                             const int32_t *src, const int32_t *rep, int Kpad)
+{
+    float *cmax = (float *)calloc((size_t)K, sizeof(float));
+    for (int i = 0; i < M; ++i)
+        for (int j = 0; j < K; ++j) {
+            float t = fabsf(X[(size_t)i * ldx + j]);
+            if (t > cmax[j]) cmax[j] = t;
+        }
+    float a = 0.0f;
+    for (int p = 0; p < Kpad; ++p) {
+        int j = src[p];
+        if (j < 0) continue;
+        float t = cmax[j] / (float)rep[p];
+        if (t > a) a = t;
+    }
+    free(cmax);
+    return a;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Flatten + quantize the activation (Eq. 3 in the equal-split form, then Eq. 1).
+ * Slot p of row i holds x[i, src[p]] / rep[p]; dividing that by s_x = a'/qmax is carried out as
+ * one fp32 multiply by m_p = fl32( qmax / (rep[p] * a') ) (formed in float64, rounded once),
+ * then round-half-even, then clamp to [qmin, qmax]; padding slots hold 0.
+ * a' is the absmax of the flattened tensor: the caller passes either the dynamic value from
+ * fqo_act_absmax_dynamic or a static (calibrated) one.  a' = 0 gives all zeros and s_x = 1.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_flatten_quant_act(const float *X, int M, int K, int ldx,
+                          const int32_t *src, const int32_t *rep, int Kpad, int bits,
+                          float a_prime, int8_t *Xq_out /* M x Kpad */, float *s_x_out)
+{
+    if (!X || !src || !rep || !Xq_out || !s_x_out || M <= 0 || K <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    if (bits != 8 && bits != 4) return FQO_ERR_ARG;
+    if (!(a_prime >= 0.0f) || isinf(a_prime)) return FQO_ERR_ARG;
+    int qmax = qmax_of(bits);
+    *s_x_out = (a_prime == 0.0f) ? 1.0f : (float)((double)a_prime / (double)qmax);
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i) {
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p];
+            int q = 0;
+            if (j >= 0 && a_prime != 0.0f) {
+                float m = (float)((double)qmax / ((double)rep[p] * (double)a_prime));
+                float prod = X[(size_t)i * ldx + j] * m;      /* one IEEE fp32 multiply */
+                q = round_clamp(prod, bits);
+            }
+            Xq_out[(size_t)i * Kpad + p] = (int8_t)q;
+        }
+    }
+    return FQO_OK;
+}
+
+/* The unquantized flatten, float64, for the invariants (X'W' = XW, max|x'| <= T):
+ * x'[i,p] = x[i,src[p]] / rep[p]; padding 0. */
+void fqo_flatten_float(const float *X, int M, int K, int ldx, const int32_t *src,
+                       const int32_t *rep, int Kpad, double *Xf_out /* M x Kpad */)
+{
+    (void)K;
+    for (int i = 0; i < M; ++i)
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p];
+            Xf_out[(size_t)i * Kpad + p] = (j >= 0) ? (double)X[(size_t)i * ldx + j] / (double)rep[p] : 0.0;
+        }
+}
+
+/* The unquantized weight repeat (Eq. 4), float64: W'[n,p] = W[n,src[p]]; padding 0. */
+void fqo_repeat_weights_float(const float *W, int N, int K, const int32_t *src, int Kpad,
+                              double *Wf_out /* N x Kpad */)
+{
+    for (int n = 0; n < N; ++n)
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p];
+            Wf_out[(size_t)n * Kpad + p] = (j >= 0) ? (double)W[(size_t)n * K + j] : 0.0;
+        }
+}
+
+/* The paper's own per-element split (Eq. 3 as printed, extended to negative values by
+ * working on |x| and restoring the sign): slot e of channel j (e = 0 is the original
+ * position, e >= 1 the appended copies in order) receives sign(x) * clamp(|x| - e*T, 0, T),
+ * i.e. floor(|x|/T) slots hold T and the next one holds the remainder.  float64.
+ * Used by the tests to show that both split rules satisfy the same two invariants. */
+void fqo_flatten_float_peel(const float *X, int M, int K, int ldx, const int32_t *src,
+                            int Kpad, double T, double *Xf_out /* M x Kpad */)
+{
+    int *seen = (int *)malloc((size_t)K * sizeof(int));
+    for (int i = 0; i < M; ++i) {
+        memset(seen, 0, (size_t)K * sizeof(int));
+        /* e for slot p = number of earlier slots with the same source, taking the original
+         * slot (p < K) first and appended slots after it in increasing p */
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p];
+            double v = 0.0;
+            if (j >= 0) {
+                int e = seen[j]++;
+                double x = (double)X[(size_t)i * ldx + j];
+                double mag = fabs(x) - (double)e * T;
+                if (mag < 0.0) mag = 0.0;
+                if (mag > T) mag = T;
+                v = (x < 0.0) ? -mag : mag;
+            }
+            Xf_out[(size_t)i * Kpad + p] = v;
+        }
+    }
+    free(seen);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * INT4 storage: two's-complement nibbles, two per byte along the flattened-channel axis,
+ * even index in the low nibble.  (The paper leaves the storage format to its GEMM library;
+ * this is the reading taken.)
+ * ---------------------------------------------------------------------------------------- */
+int fqo_pack_i4(const int8_t *q, long long rows, int Kpad, uint8_t *out /* rows x Kpad/2 */)
+{
+    if (!q || !out || Kpad <= 0 || (Kpad & 1)) return FQO_ERR_ARG;
+    for (long long r = 0; r < rows; ++r)
+        for (int b = 0; b < Kpad / 2; ++b) {
+            int lo = q[r * Kpad + 2 * b], hi = q[r * Kpad + 2 * b + 1];
+            if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return FQO_ERR_ARG;
+            out[r * (Kpad / 2) + b] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
+        }
+    return FQO_OK;
+}
+
+int fqo_unpack_i4(const uint8_t *packed, long long rows, int Kpad, int8_t *q /* rows x Kpad */)
+{
+    if (!q || !packed || Kpad <= 0 || (Kpad & 1)) return FQO_ERR_ARG;
+    for (long long r = 0; r < rows; ++r)
+        for (int b = 0; b < Kpad / 2; ++b) {
+            int byte = packed[r * (Kpad / 2) + b];
+            int lo = byte & 0xF, hi = (byte >> 4) & 0xF;
+            q[r * Kpad + 2 * b] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+            q[r * Kpad + 2 * b + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+        }
+    return FQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Integer GEMM with int32 accumulation: acc[i,n] = sum_p Xq[i,p] * Wq[n,p].
+ * Rows [row0, row0+rows) of the M x N result are produced (rows = M, row0 = 0 for all of it),
+ * so that a bounded sample of a large problem can be computed.  acc_out holds `rows` rows.
+ * The running sum is kept in int64 and checked against the int32 range.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_gemm_i32(const int8_t *Xq, const int8_t *Wq, int M, int N, int Kpad,
+                 int row0, int rows, int32_t *acc_out /* rows x N */)
+{
+    if (!Xq || !Wq || !acc_out || M <= 0 || N <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    if (row0 < 0 || rows < 0 || row0 + rows > M) return FQO_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int i = 0; i < rows; ++i) {
+        const int8_t *x = Xq + (size_t)(row0 + i) * Kpad;
+        for (int n = 0; n < N; ++n) {
+            const int8_t *w = Wq + (size_t)n * Kpad;
+            int64_t s = 0;
+            for (int p = 0; p < Kpad; ++p) s += (int32_t)x[p] * (int32_t)w[p];
+            if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+            acc_out[(size_t)i * N + n] = (int32_t)s;
+        }
+    }
+    return bad ? FQO_ERR_OVERFLOW : FQO_OK;
+}
+
+/* One accumulator, for sampled checks at full size. */
+int32_t fqo_dot_i32(const int8_t *x, const int8_t *w, int Kpad)
+{
+    int64_t s = 0;
+    for (int p = 0; p < Kpad; ++p) s += (int32_t)x[p] * (int32_t)w[p];
+    return (int32_t)s;
+}
+
+/* Dequantize (the inverse of Eq. 1 applied to the product): y = acc * s_x * s_w, float64. */
+void fqo_dequant(const int32_t *acc, long long count, float s_x, float s_w, double *y_out)
+{
+    for (long long i = 0; i < count; ++i)
+        y_out[i] = (double)acc[i] * (double)s_x * (double)s_w;
+}
+
+/* Unquantized reference product Y = X W^T in float64 (what the layer approximates). */
+void fqo_linear_f64(const float *X, const float *W, int M, int N, int K, int ldx, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i)
+        for (int n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int j = 0; j < K; ++j) s += (double)X[(size_t)i * ldx + j] * (double)W[(size_t)n * K + j];
+            Y[(size_t)i * N + n] = s;
+        }
+}
+
+/* Product of two float64 row-major operands sharing their contiguous axis:
+ * Y[i,n] = sum_p A[i,p] * B[n,p].  Used for X'W' in the identity test. */
+void fqo_matmul_nt_f64(const double *A, const double *B, int M, int N, int Kpad, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i)
+        for (int n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int p = 0; p < Kpad; ++p) s += A[(size_t)i * Kpad + p] * B[(size_t)n * Kpad + p];
+            Y[(size_t)i * N + n] = s;
+        }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The whole layer on rows [row0, row0+rows): dynamic or static activation scale (a_static < 0
+ * selects dynamic), flatten-quantize, (pack/unpack for k = 4), integer GEMM, dequantize.
+ * Wq / s_w come from fqo_flatten_weights.  The dynamic absmax is always taken over ALL M rows
+ * (it is a per-tensor quantity) even when only a sample of rows is multiplied.
+ * Outputs: acc (rows x N int32), y (rows x N float64), s_x.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_linear(const float *X, int M, int K, int ldx, const int32_t *src, const int32_t *rep,
+               int Kpad, const int8_t *Wq, float s_w, int N, int bits, float a_static,
+               int row0, int rows, int32_t *acc_out, double *y_out, float *s_x_out)
+{
+    if (row0 < 0 || rows <= 0 || row0 + rows > M) return FQO_ERR_ARG;
+    float a_prime = (a_static >= 0.0f) ? a_static
+                                       : fqo_act_absmax_dynamic(X, M, K, ldx, src, rep, Kpad);
+    int8_t *Xq = (int8_t *)malloc((size_t)rows * Kpad);
+    if (!Xq) return FQO_ERR_ARG;
+    int rc = fqo_flatten_quant_act(X + (size_t)row0 * ldx, rows, K, ldx, src, rep, Kpad, bits,
+                                   a_prime, Xq, s_x_out);
+    if (rc == FQO_OK && bits == 4) {
+        /* through the packed representation and back, as the stored tensors are */
+        uint8_t *pk = (uint8_t *)malloc((size_t)rows * (Kpad / 2));
+        rc = fqo_pack_i4(Xq, rows, Kpad, pk);
+        if (rc == FQO_OK) rc = fqo_unpack_i4(pk, rows, Kpad, Xq);
+        free(pk);
+    }
+    if (rc == FQO_OK) rc = fqo_gemm_i32(Xq, Wq, rows, N, Kpad, 0, rows, acc_out);
+    if (rc == FQO_OK && y_out) fqo_dequant(acc_out, (long long)rows * N, *s_x_out, s_w, y_out);
+    free(Xq);
+    return rc;
+}

@@ -1,0 +1,234 @@
+"""ctypes front end of the CPU oracle (oracle/fq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg.  It holds no arithmetic of the method: it marshals NumPy arrays into the C
+functions, which are the definitions written from the paper (arXiv 2402.17985, Sec. 2.1 Eq. 1,
+Sec. 4.1 Eq. 2-4, Sec. 5.1).  Nothing in the GPU package imports this module.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = ctypes.CDLL(path)
+        _lib.fqo_absmax.restype = ctypes.c_float
+        _lib.fqo_act_absmax_dynamic.restype = ctypes.c_float
+        _lib.fqo_dot_i32.restype = ctypes.c_int32
+    return _lib
+
+
+def _p(a, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what} failed with code {rc}")
+
+
+def num_threads() -> int:
+    return int(lib().fqo_num_threads())
+
+
+def plan(chmax, T, align=32):
+    """Eq. 2 / Eq. 3 index layout / padding.  Returns (src, rep, Kprime, Kpad)."""
+    chmax = _f32(chmax)
+    K = chmax.shape[0]
+    kp, kpad = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().fqo_plan(_p(chmax, ctypes.c_float), K, ctypes.c_float(T), align, None, None, 0,
+                        ctypes.byref(kp), ctypes.byref(kpad))
+    _check(rc, "fqo_plan(size query)")
+    src = np.empty(kpad.value, dtype=np.int32)
+    rep = np.empty(kpad.value, dtype=np.int32)
+    rc = lib().fqo_plan(_p(chmax, ctypes.c_float), K, ctypes.c_float(T), align,
+                        _p(src, ctypes.c_int32), _p(rep, ctypes.c_int32), kpad.value,
+                        ctypes.byref(kp), ctypes.byref(kpad))
+    _check(rc, "fqo_plan")
+    return src, rep, kp.value, kpad.value
+
+
+def absmax(v) -> float:
+    v = _f32(v).reshape(-1)
+    return float(lib().fqo_absmax(_p(v, ctypes.c_float), ctypes.c_longlong(v.size)))
+
+
+def flatten_weights(W, src, bits):
+    """Eq. 1 + Eq. 4.  Returns (Wq int8 [N, Kpad], s_w)."""
+    W = _f32(W)
+    N, K = W.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    Kpad = src.shape[0]
+    out = np.empty((N, Kpad), dtype=np.int8)
+    s_w = ctypes.c_float(0)
+    rc = lib().fqo_flatten_weights(_p(W, ctypes.c_float), N, K, _p(src, ctypes.c_int32), Kpad, bits,
+                                   _p(out, ctypes.c_int8), ctypes.byref(s_w))
+    _check(rc, "fqo_flatten_weights")
+    return out, np.float32(s_w.value)
+
+
+def act_absmax_dynamic(X, src, rep) -> np.float32:
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    rep = np.ascontiguousarray(rep, dtype=np.int32)
+    return np.float32(lib().fqo_act_absmax_dynamic(_p(X, ctypes.c_float), M, K, K,
+                                                   _p(src, ctypes.c_int32), _p(rep, ctypes.c_int32),
+                                                   src.shape[0]))
+
+
+def flatten_quant_act(X, src, rep, bits, a_prime):
+    """Eq. 3 (equal split) + Eq. 1.  Returns (Xq int8 [M, Kpad], s_x)."""
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    rep = np.ascontiguousarray(rep, dtype=np.int32)
+    Kpad = src.shape[0]
+    out = np.empty((M, Kpad), dtype=np.int8)
+    s_x = ctypes.c_float(0)
+    rc = lib().fqo_flatten_quant_act(_p(X, ctypes.c_float), M, K, K, _p(src, ctypes.c_int32),
+                                     _p(rep, ctypes.c_int32), Kpad, bits, ctypes.c_float(a_prime),
+                                     _p(out, ctypes.c_int8), ctypes.byref(s_x))
+    _check(rc, "fqo_flatten_quant_act")
+    return out, np.float32(s_x.value)
+
+
+def flatten_float(X, src, rep):
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    rep = np.ascontiguousarray(rep, dtype=np.int32)
+    out = np.empty((M, src.shape[0]), dtype=np.float64)
+    lib().fqo_flatten_float(_p(X, ctypes.c_float), M, K, K, _p(src, ctypes.c_int32),
+                            _p(rep, ctypes.c_int32), src.shape[0], _p(out, ctypes.c_double))
+    return out
+
+
+def flatten_float_peel(X, src, T):
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    out = np.empty((M, src.shape[0]), dtype=np.float64)
+    lib().fqo_flatten_float_peel(_p(X, ctypes.c_float), M, K, K, _p(src, ctypes.c_int32),
+                                 src.shape[0], ctypes.c_double(T), _p(out, ctypes.c_double))
+    return out
+
+
+def repeat_weights_float(W, src):
+    W = _f32(W)
+    N, K = W.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    out = np.empty((N, src.shape[0]), dtype=np.float64)
+    lib().fqo_repeat_weights_float(_p(W, ctypes.c_float), N, K, _p(src, ctypes.c_int32),
+                                   src.shape[0], _p(out, ctypes.c_double))
+    return out
+
+
+def pack_i4(q):
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    rows, Kpad = q.shape
+    out = np.empty((rows, Kpad // 2), dtype=np.uint8)
+    rc = lib().fqo_pack_i4(_p(q, ctypes.c_int8), ctypes.c_longlong(rows), Kpad, _p(out, ctypes.c_uint8))
+    _check(rc, "fqo_pack_i4")
+    return out
+
+
+def unpack_i4(packed):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    rows, half = packed.shape
+    out = np.empty((rows, 2 * half), dtype=np.int8)
+    rc = lib().fqo_unpack_i4(_p(packed, ctypes.c_uint8), ctypes.c_longlong(rows), 2 * half,
+                             _p(out, ctypes.c_int8))
+    _check(rc, "fqo_unpack_i4")
+    return out
+
+
+def gemm_i32(Xq, Wq, row0=0, rows=None):
+    """acc[i, n] = sum_p Xq[i, p] * Wq[n, p] for rows [row0, row0+rows)."""
+    Xq = np.ascontiguousarray(Xq, dtype=np.int8)
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    M, Kpad = Xq.shape
+    N, Kpad2 = Wq.shape
+    assert Kpad == Kpad2
+    if rows is None:
+        rows = M - row0
+    out = np.empty((rows, N), dtype=np.int32)
+    rc = lib().fqo_gemm_i32(_p(Xq, ctypes.c_int8), _p(Wq, ctypes.c_int8), M, N, Kpad, row0, rows,
+                            _p(out, ctypes.c_int32))
+    _check(rc, "fqo_gemm_i32")
+    return out
+
+
+def dot_i32(x, w) -> int:
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    assert x.shape == w.shape and x.ndim == 1
+    return int(lib().fqo_dot_i32(_p(x, ctypes.c_int8), _p(w, ctypes.c_int8), x.shape[0]))
+
+
+def dequant(acc, s_x, s_w):
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    out = np.empty(acc.shape, dtype=np.float64)
+    lib().fqo_dequant(_p(acc, ctypes.c_int32), ctypes.c_longlong(acc.size), ctypes.c_float(s_x),
+                      ctypes.c_float(s_w), _p(out, ctypes.c_double))
+    return out
+
+
+def linear_f64(X, W):
+    X = _f32(X)
+    W = _f32(W)
+    M, K = X.shape
+    N = W.shape[0]
+    out = np.empty((M, N), dtype=np.float64)
+    lib().fqo_linear_f64(_p(X, ctypes.c_float), _p(W, ctypes.c_float), M, N, K, K, _p(out, ctypes.c_double))
+    return out
+
+
+def matmul_nt_f64(A, B):
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    B = np.ascontiguousarray(B, dtype=np.float64)
+    M, Kp = A.shape
+    N = B.shape[0]
+    out = np.empty((M, N), dtype=np.float64)
+    lib().fqo_matmul_nt_f64(_p(A, ctypes.c_double), _p(B, ctypes.c_double), M, N, Kp, _p(out, ctypes.c_double))
+    return out
+
+
+def linear(X, src, rep, Wq, s_w, bits, a_static=None, row0=0, rows=None, want_y=True):
+    """The whole layer on rows [row0, row0+rows).  Returns (acc int32, y float64 or None, s_x)."""
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    rep = np.ascontiguousarray(rep, dtype=np.int32)
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    N, Kpad = Wq.shape
+    assert Kpad == src.shape[0]
+    if rows is None:
+        rows = M - row0
+    acc = np.empty((rows, N), dtype=np.int32)
+    y = np.empty((rows, N), dtype=np.float64) if want_y else None
+    s_x = ctypes.c_float(0)
+    rc = lib().fqo_linear(_p(X, ctypes.c_float), M, K, K, _p(src, ctypes.c_int32), _p(rep, ctypes.c_int32),
+                          Kpad, _p(Wq, ctypes.c_int8), ctypes.c_float(s_w), N, bits,
+                          ctypes.c_float(-1.0 if a_static is None else a_static), row0, rows,
+                          _p(acc, ctypes.c_int32), _p(y, ctypes.c_double) if want_y else None,
+                          ctypes.byref(s_x))
+    _check(rc, "fqo_linear")
+    return acc, y, np.float32(s_x.value)
