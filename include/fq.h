@@ -1,0 +1,187 @@
+/*
+ * fq.h — C ABI of the FlattenQuant per-tensor-quantized linear layer for AMD MI355X (gfx950).
+ *
+ * The layer (arXiv 2402.17985):
+ *   1. flatten the activation: an input channel j whose calibrated max|x| exceeds the
+ *      truncation threshold T is spread over n_j channels and the matching weight channel is
+ *      repeated n_j times, so that X'W' = XW (Sec. 4.1, Eq. 2-4);
+ *   2. quantize X' and W' per tensor to INT8 or INT4 (Sec. 2.1, Eq. 1);
+ *   3. multiply in integers with int32 accumulation and scale the result back by s_x * s_w
+ *      (Sec. 5.1 "Implementation": quantized linear layers on INT8 / INT4 GEMM kernels).
+ *
+ * Shapes and layouts
+ *   X    activations  [M, K]      row-major, K contiguous, row stride ldx elements
+ *   W    weights      [N, K]      row-major (the nn.Linear storage layout).  The paper writes
+ *                                 Y = X W; its "weight channel j" is column j of this array.
+ *   map  src_idx[p], rep[p], p in [0, Kpad): flattened slot p reads input channel src_idx[p]
+ *        (-1 = padding slot, value 0) and that channel has rep[p] = n_j copies in total.
+ *   Xq   [M, Kpad] int8, or [M, Kpad/2] bytes for INT4 (two's-complement nibbles, even slot in
+ *        the low nibble); Wq likewise [N, Kpad] / [N, Kpad/2].  Rows are densely packed.
+ *   Y    [M, N] row-major, row stride ldy elements.
+ *   Kpad must be a multiple of 32 (Sec. 5.1 pads the flattened channel count to a multiple of 32).
+ *
+ * Conventions common to every call
+ *   - Returns FQ_OK (0) or an FQ_ERR_* code; fq_last_error_string() (thread-local) says why.
+ *   - Pointers are DEVICE pointers unless the parameter name ends in _host.
+ *   - All buffers are caller-owned.  The library allocates nothing, frees nothing and never
+ *     synchronizes: every kernel is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns immediately.
+ *   - Arguments are validated on the host before anything is launched: on error nothing has
+ *     been enqueued.  Device-resident maps cannot be validated from the host; kernels treat
+ *     any src_idx outside [0, K) as a padding slot, so a bad map cannot cause an
+ *     out-of-bounds access.
+ *   - Inputs must be finite.  Results are deterministic (bit-identical from run to run).
+ *   - Device pointers must be 16-byte aligned (anything from hipMalloc is).
+ */
+#ifndef FQ_H
+#define FQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FQ_F32 = 0,
+    FQ_F16 = 1,
+    FQ_BF16 = 2,
+    FQ_I32 = 3   /* raw int32 accumulators (GEMM output only; for verification) */
+} fq_dtype;
+
+enum {
+    FQ_OK = 0,
+    FQ_ERR_NULL = 1,       /* a required pointer is NULL */
+    FQ_ERR_SHAPE = 2,      /* non-positive size, Kpad not a multiple of 32, stride too small, capacity too small */
+    FQ_ERR_DTYPE = 3,      /* dtype / bit width not supported by this call */
+    FQ_ERR_RANGE = 4,      /* T <= 0 or not finite, channel maximum negative / NaN / Inf, size beyond int32 or accumulator bounds */
+    FQ_ERR_ALIGN = 5,      /* a device pointer is not 16-byte aligned */
+    FQ_ERR_HIP = 6,        /* a HIP launch failed */
+    FQ_ERR_WORKSPACE = 7   /* workspace_bytes smaller than the matching *_workspace_bytes() */
+};
+
+/* Human-readable reason of the last error on the calling thread ("" if none). */
+const char* fq_last_error_string(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int fq_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_flatten_plan — channel maxima and T -> the channel index / repeat map.   HOST function.
+ * Sec. 4.1 Eq. 2 (number of channels per input channel), Eq. 3 (index layout), Sec. 5.1 (padding).
+ *
+ *   n_j = max(1, ceil(chmax_j / T))  (ratio in float64), E_j = n_j - 1 extra channels,
+ *   Kprime = K + sum_j E_j,  Kpad = Kprime rounded up to a multiple of `align`.
+ *   Slots 0..K-1 keep the original channels (src_idx[p] = p).  The E_j extras of channel j occupy
+ *   slots K + sum_{k<j} E_k ... in increasing j.  Slots Kprime..Kpad-1 are padding (src -1, rep 0).
+ *   (Eq. 2 prints floor(max/T) extra channels; that equals n_j - 1 except when max is an exact
+ *   multiple of T, where the printed form would add one channel that is always zero.)
+ *
+ * chmax_host  [K] fp32, host; each >= 0 and finite.       T > 0, finite.
+ * align       > 0; must be a multiple of 32 for the map to be usable by the device calls.
+ * src_idx_host, rep_host  [cap] int32, host, written up to Kpad entries.
+ * cap = 0: size query only (src/rep may be NULL); Kprime_out / Kpad_out (either may be NULL)
+ *          are written.  cap > 0 and cap < Kpad: FQ_ERR_SHAPE, sizes still written.
+ * ------------------------------------------------------------------------------------------- */
+int fq_flatten_plan(const float* chmax_host, int K, float T, int align,
+                    int32_t* src_idx_host, int32_t* rep_host, int cap,
+                    int* Kprime_out, int* Kpad_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_flatten_weights — offline: quantize W per tensor and repeat its channels by the map.
+ * Eq. 1 (s_w = max|W| / qmax, qmax = 2^(bits-1) - 1), Eq. 4 (repeat), done "during model
+ * quantization" (Fig. 3).
+ *
+ *   m_w = fl32(qmax / max|W|) (quotient in float64),  Wq[n,j] = clamp(rne(W[n,j] * m_w), qmin, qmax),
+ *   Wq_out[n,p] = Wq[n, src_idx[p]], 0 in padding slots; bits = 4 packs two slots per byte.
+ *   All-zero W: Wq_out = 0, s_w = 1.
+ *
+ * W        [N, K] device, w_dtype in {FQ_F32, FQ_F16, FQ_BF16}, row stride ldw >= K elements.
+ * Wq_out   [N, Kpad] int8 (bits 8) or [N, Kpad/2] uint8 (bits 4), device.
+ * s_w_out  one fp32, device.
+ * workspace  fq_weights_workspace_bytes(K, Kpad) bytes, device, 16-byte aligned; contents undefined after.
+ * ------------------------------------------------------------------------------------------- */
+int fq_flatten_weights(const void* W, int w_dtype, int N, int K, int ldw,
+                       const int32_t* src_idx, int Kpad, int bits,
+                       void* Wq_out, float* s_w_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+size_t fq_weights_workspace_bytes(int K, int Kpad);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_flatten_quant_act — inference time: fused flatten (gather + equal split) and per-tensor
+ * quantization of the activation.  Eq. 3 in its equal-split form (each of the n_j copies of
+ * channel j holds x / n_j), then Eq. 1.
+ *
+ *   a' = absmax of the flattened tensor:
+ *        static  (absmax_in != NULL): *absmax_in, e.g. the calibrated bound T — the paper's
+ *                 setting (Table 2: per-tensor static);
+ *        dynamic (absmax_in == NULL): max_p fl32( max_i |X[i,src_idx[p]]| / rep[p] ), taken from X.
+ *   s_x = fl32(a' / qmax),  m_p = fl32(qmax / (rep[p] * a'))  (both formed in float64),
+ *   Xq_out[i,p] = clamp(rne(X[i,src_idx[p]] * m_p), qmin, qmax); 0 in padding slots;
+ *   bits = 4 packs two slots per byte.   a' = 0: Xq_out = 0, s_x = 1.
+ *
+ * X         [M, K] device, x_dtype in {FQ_F32, FQ_F16, FQ_BF16}, row stride ldx >= K elements;
+ *           ldx * sizeof(element) must be a multiple of 16.
+ * Xq_out    [M, Kpad] int8 or [M, Kpad/2] uint8, device.
+ * s_x_out   one fp32, device.
+ * workspace fq_act_workspace_bytes(K, Kpad) bytes, device, 16-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx,
+                         const int32_t* src_idx, const int32_t* rep, int Kpad, int bits,
+                         const float* absmax_in, void* Xq_out, float* s_x_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+size_t fq_act_workspace_bytes(int K, int Kpad);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_gemm_i8 / fq_gemm_i4 — integer GEMM with int32 accumulation and the fused per-tensor
+ * dequantize epilogue (Sec. 5.1; the inverse of Eq. 1 applied to the product).
+ *
+ *   acc[i,n] = sum_{p < Kpad} Xq[i,p] * Wq[n,p]                      (exact, int32)
+ *   Y[i,n]   = round_to_y_dtype( fl32(acc[i,n]) * fl32(*s_x * *s_w) )   for F32 / F16 / BF16
+ *   Y[i,n]   = acc[i,n]                                                for FQ_I32 (scales may be NULL)
+ *
+ * fq_gemm_i4 takes both operands packed two per byte ([M, Kpad/2], [N, Kpad/2]); they stay
+ * packed in HBM and LDS and are widened to int8 in registers (gfx950 has no 4-bit MFMA).
+ * M, N >= 1 arbitrary; Kpad a multiple of 32 with Kpad * 128 * 128 < 2^31.
+ * s_x, s_w  device scalars read by the kernel (no host synchronization).
+ * Y         device, row stride ldy >= N elements.
+ * ------------------------------------------------------------------------------------------- */
+int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad,
+               const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy, void* stream);
+int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad,
+               const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_linear — the end-to-end inference call: fq_flatten_quant_act followed by fq_gemm_i8 /
+ * fq_gemm_i4 on one stream.  Wq / s_w come from fq_flatten_weights with the same map and bits.
+ * workspace  fq_linear_workspace_bytes(M, K, Kpad, bits) bytes, device, 16-byte aligned; holds
+ *            the quantized activation, the per-slot multipliers and s_x.
+ * ------------------------------------------------------------------------------------------- */
+int fq_linear(const void* X, int x_dtype, int M, int K, int ldx,
+              const int32_t* src_idx, const int32_t* rep, int Kpad,
+              const void* Wq, const float* s_w, int N, int bits,
+              const float* absmax_in, void* Y, int y_dtype, int ldy,
+              void* workspace, size_t workspace_bytes, void* stream);
+size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_gemm_bf16 — the unquantized baseline the paper compares against (Table 5, "Gemm (FP16)"):
+ * Y = X W^T with bf16 operands, fp32 accumulation on the bf16 MFMA, bf16 output.
+ * X [M, K], W [N, K] device bf16, dense rows; K a multiple of 8.  Y [M, N] bf16, row stride ldy.
+ * ------------------------------------------------------------------------------------------- */
+int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * fq_gemm_select — tuning hook for benchmarks: force the tile variant used by fq_gemm_i8 /
+ * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
+ *   0: 256x256 tile, 128-byte k-stages, 8 waves    1: 256x256 tile, 64-byte k-stages, 8 waves
+ *   2: 128x128 tile,  64-byte k-stages, 4 waves    3: 256x128 tile, 128-byte k-stages, 8 waves
+ * Every variant computes the same values.  Returns FQ_ERR_RANGE for an unknown variant.
+ * ------------------------------------------------------------------------------------------- */
+int fq_gemm_select(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FQ_H */

@@ -1,0 +1,200 @@
+"""Thin Python binding of libfq.so (include/fq.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the C ABI.
+PyTorch tensors are used as device buffers (`data_ptr()`) and for the current stream; nothing is
+computed in PyTorch.  There is no fallback: if libfq.so is missing, loading raises.
+"""
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfq.so")
+
+FQ_F32, FQ_F16, FQ_BF16, FQ_I32 = 0, 1, 2, 3
+FQ_OK = 0
+ERR_NAMES = {1: "FQ_ERR_NULL", 2: "FQ_ERR_SHAPE", 3: "FQ_ERR_DTYPE", 4: "FQ_ERR_RANGE", 5: "FQ_ERR_ALIGN",
+             6: "FQ_ERR_HIP", 7: "FQ_ERR_WORKSPACE"}
+
+# every entry point include/fq.h declares
+SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_weights",
+           "fq_weights_workspace_bytes", "fq_flatten_quant_act", "fq_act_workspace_bytes", "fq_gemm_i8",
+           "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select"]
+
+
+class FqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{ERR_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libfq.so (built in-tree by paper_2402_17985_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2402_17985_amd.build` "
+                                "(there is no CPU or PyTorch fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    c_int, c_float, c_size_t, vp = ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_void_p
+    L.fq_last_error_string.restype = ctypes.c_char_p
+    L.fq_last_error_string.argtypes = []
+    L.fq_version.restype = c_int
+    L.fq_gemm_select.argtypes = [c_int]
+    L.fq_flatten_plan.argtypes = [vp, c_int, c_float, c_int, vp, vp, c_int, ctypes.POINTER(c_int),
+                                  ctypes.POINTER(c_int)]
+    L.fq_flatten_weights.argtypes = [vp, c_int, c_int, c_int, c_int, vp, c_int, c_int, vp, vp, vp, c_size_t, vp]
+    L.fq_weights_workspace_bytes.restype = c_size_t
+    L.fq_weights_workspace_bytes.argtypes = [c_int, c_int]
+    L.fq_flatten_quant_act.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, vp, vp, vp, vp,
+                                       c_size_t, vp]
+    L.fq_act_workspace_bytes.restype = c_size_t
+    L.fq_act_workspace_bytes.argtypes = [c_int, c_int]
+    for f in (L.fq_gemm_i8, L.fq_gemm_i4):
+        f.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, c_int, c_int, vp]
+    L.fq_linear.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, c_int, c_int, vp, vp, c_int,
+                            c_int, vp, c_size_t, vp]
+    L.fq_linear_workspace_bytes.restype = c_size_t
+    L.fq_linear_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
+    L.fq_gemm_bf16.argtypes = [vp, vp, c_int, c_int, c_int, vp, c_int, vp]
+    for name in SYMBOLS:
+        getattr(L, name)
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != FQ_OK:
+        raise FqError(rc, lib().fq_last_error_string().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    return {torch.float32: FQ_F32, torch.float16: FQ_F16, torch.bfloat16: FQ_BF16, torch.int32: FQ_I32}[t.dtype]
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return _torch().cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dev2d(t, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name} must be 2-D with a contiguous last dimension")
+    return t
+
+
+# ------------------------------------------------------------------------------------------
+# entry points (same names as the C ABI)
+# ------------------------------------------------------------------------------------------
+def fq_version() -> int:
+    return lib().fq_version()
+
+
+def fq_gemm_select(variant: int) -> None:
+    _check(lib().fq_gemm_select(variant))
+
+
+def fq_flatten_plan(chmax: np.ndarray, T: float, align: int = 32) -> Tuple[np.ndarray, np.ndarray, int, int]:
+    """Host call.  Returns (src_idx int32 [Kpad], rep int32 [Kpad], Kprime, Kpad)."""
+    chmax = np.ascontiguousarray(chmax, dtype=np.float32)
+    K = chmax.shape[0]
+    kp, kpad = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().fq_flatten_plan(chmax.ctypes.data, K, T, align, None, None, 0, ctypes.byref(kp), ctypes.byref(kpad)))
+    src = np.empty(kpad.value, dtype=np.int32)
+    rep = np.empty(kpad.value, dtype=np.int32)
+    _check(lib().fq_flatten_plan(chmax.ctypes.data, K, T, align, src.ctypes.data, rep.ctypes.data, kpad.value,
+                                 ctypes.byref(kp), ctypes.byref(kpad)))
+    return src, rep, kp.value, kpad.value
+
+
+def fq_weights_workspace_bytes(K: int, Kpad: int) -> int:
+    return lib().fq_weights_workspace_bytes(K, Kpad)
+
+
+def fq_act_workspace_bytes(K: int, Kpad: int) -> int:
+    return lib().fq_act_workspace_bytes(K, Kpad)
+
+
+def fq_linear_workspace_bytes(M: int, K: int, Kpad: int, bits: int) -> int:
+    return lib().fq_linear_workspace_bytes(M, K, Kpad, bits)
+
+
+def fq_flatten_weights(W, src_idx, bits: int, Wq_out, s_w_out, workspace, stream=None) -> None:
+    _dev2d(W, "W")
+    N, K = W.shape
+    Kpad = src_idx.numel()
+    _check(lib().fq_flatten_weights(W.data_ptr(), _dtype_code(W), N, K, W.stride(0), src_idx.data_ptr(), Kpad, bits,
+                                    Wq_out.data_ptr(), s_w_out.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fq_flatten_quant_act(X, src_idx, rep, bits: int, Xq_out, s_x_out, workspace, absmax_in=None, stream=None) -> None:
+    _dev2d(X, "X")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    _check(lib().fq_flatten_quant_act(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(),
+                                      rep.data_ptr(), Kpad, bits, _ptr(absmax_in), Xq_out.data_ptr(),
+                                      s_x_out.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def _gemm(fn, Xq, Wq, M, N, Kpad, s_x, s_w, Y, stream):
+    _dev2d(Y, "Y")
+    _check(fn(Xq.data_ptr(), Wq.data_ptr(), M, N, Kpad, _ptr(s_x), _ptr(s_w), Y.data_ptr(), _dtype_code(Y),
+              Y.stride(0), _stream(stream)))
+
+
+def fq_gemm_i8(Xq, Wq, s_x, s_w, Y, stream=None) -> None:
+    """Xq int8 [M, Kpad], Wq int8 [N, Kpad] -> Y [M, N] (f32/f16/bf16, or int32 raw accumulators)."""
+    M, Kpad = Xq.shape
+    N = Wq.shape[0]
+    _gemm(lib().fq_gemm_i8, Xq, Wq, M, N, Kpad, s_x, s_w, Y, stream)
+
+
+def fq_gemm_i4(Xq, Wq, s_x, s_w, Y, stream=None) -> None:
+    """Xq uint8 [M, Kpad/2], Wq uint8 [N, Kpad/2] (packed nibbles) -> Y [M, N]."""
+    M, half = Xq.shape
+    N = Wq.shape[0]
+    _gemm(lib().fq_gemm_i4, Xq, Wq, M, N, 2 * half, s_x, s_w, Y, stream)
+
+
+def fq_linear(X, src_idx, rep, Wq, s_w, bits: int, Y, workspace, absmax_in=None, stream=None) -> None:
+    _dev2d(X, "X")
+    _dev2d(Y, "Y")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    N = Wq.shape[0]
+    _check(lib().fq_linear(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(), rep.data_ptr(), Kpad,
+                           Wq.data_ptr(), s_w.data_ptr(), N, bits, _ptr(absmax_in), Y.data_ptr(), _dtype_code(Y),
+                           Y.stride(0), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                           _stream(stream)))
+
+
+def fq_gemm_bf16(X, W, Y, stream=None) -> None:
+    _dev2d(X, "X")
+    _dev2d(W, "W")
+    _dev2d(Y, "Y")
+    M, K = X.shape
+    N = W.shape[0]
+    if X.stride(0) != K or W.stride(0) != K:
+        raise ValueError("fq_gemm_bf16 needs densely packed rows")
+    _check(lib().fq_gemm_bf16(X.data_ptr(), W.data_ptr(), M, N, K, Y.data_ptr(), Y.stride(0), _stream(stream)))

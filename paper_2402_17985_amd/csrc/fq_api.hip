@@ -1,0 +1,239 @@
+// C-ABI layer of libfq: argument validation, the host-side flatten plan, and the composition
+// of the kernels into the calls declared in include/fq.h.  Nothing here allocates or synchronizes.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "fq_internal.h"
+
+namespace fq {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+void clear_error() { g_err[0] = '\0'; }
+
+int set_gemm_variant(int v);   // fq_gemm.hip
+
+namespace {
+
+bool float_dtype(int d) { return d == FQ_F32 || d == FQ_F16 || d == FQ_BF16; }
+
+// Checks shared by the calls that read a floating-point matrix [rows, K] with stride ld.
+int check_matrix(const char* what, const void* p, int dtype, int rows, int K, int ld)
+{
+    if (!p) return fail(FQ_ERR_NULL, "%s is NULL", what);
+    if (!float_dtype(dtype)) return fail(FQ_ERR_DTYPE, "%s: dtype %d is not F32/F16/BF16", what, dtype);
+    if (rows <= 0 || K <= 0) return fail(FQ_ERR_SHAPE, "%s: non-positive shape %d x %d", what, rows, K);
+    if (ld < K) return fail(FQ_ERR_SHAPE, "%s: row stride %d < K = %d", what, ld, K);
+    if (((size_t)ld * elem_size(dtype)) % 16 != 0)
+        return fail(FQ_ERR_SHAPE, "%s: row stride of %d elements is not a multiple of 16 bytes", what, ld);
+    if (!aligned16(p)) return fail(FQ_ERR_ALIGN, "%s is not 16-byte aligned", what);
+    return FQ_OK;
+}
+
+int check_map(const int32_t* src_idx, int Kpad, int bits)
+{
+    if (!src_idx) return fail(FQ_ERR_NULL, "src_idx is NULL");
+    if (bits != 8 && bits != 4) return fail(FQ_ERR_DTYPE, "bits = %d, must be 8 or 4", bits);
+    if (Kpad <= 0 || Kpad % 32 != 0) return fail(FQ_ERR_SHAPE, "Kpad = %d must be a positive multiple of 32", Kpad);
+    if (Kpad >= 131072) return fail(FQ_ERR_RANGE, "Kpad = %d: int32 accumulators could overflow (needs Kpad < 131072)", Kpad);
+    if (!aligned16(src_idx)) return fail(FQ_ERR_ALIGN, "src_idx is not 16-byte aligned");
+    return FQ_OK;
+}
+
+int check_gemm(const void* Xq, const void* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+               const void* Y, int y_dtype, int ldy)
+{
+    if (!Xq || !Wq || !Y) return fail(FQ_ERR_NULL, "Xq, Wq or Y is NULL");
+    if (y_dtype != FQ_F32 && y_dtype != FQ_F16 && y_dtype != FQ_BF16 && y_dtype != FQ_I32)
+        return fail(FQ_ERR_DTYPE, "unsupported output dtype %d", y_dtype);
+    if (y_dtype != FQ_I32 && (!s_x || !s_w)) return fail(FQ_ERR_NULL, "s_x or s_w is NULL");
+    if (M <= 0 || N <= 0) return fail(FQ_ERR_SHAPE, "non-positive shape M = %d, N = %d", M, N);
+    if (Kpad <= 0 || Kpad % 32 != 0) return fail(FQ_ERR_SHAPE, "Kpad = %d must be a positive multiple of 32", Kpad);
+    if (Kpad >= 131072) return fail(FQ_ERR_RANGE, "Kpad = %d: int32 accumulators could overflow (needs Kpad < 131072)", Kpad);
+    if (ldy < N) return fail(FQ_ERR_SHAPE, "ldy = %d < N = %d", ldy, N);
+    if (!aligned16(Xq) || !aligned16(Wq)) return fail(FQ_ERR_ALIGN, "Xq or Wq is not 16-byte aligned");
+    return FQ_OK;
+}
+
+}  // namespace
+}  // namespace fq
+
+using namespace fq;
+
+extern "C" {
+
+const char* fq_last_error_string(void) { return g_err; }
+
+int fq_version(void) { return 100; }
+
+int fq_gemm_select(int variant)
+{
+    clear_error();
+    return set_gemm_variant(variant);
+}
+
+int fq_flatten_plan(const float* chmax_host, int K, float T, int align, int32_t* src_idx_host,
+                    int32_t* rep_host, int cap, int* Kprime_out, int* Kpad_out)
+{
+    clear_error();
+    if (!chmax_host) return fail(FQ_ERR_NULL, "chmax is NULL");
+    if (K <= 0 || align <= 0 || cap < 0) return fail(FQ_ERR_SHAPE, "K = %d, align = %d, cap = %d", K, align, cap);
+    if (!(T > 0.0f) || std::isinf(T)) return fail(FQ_ERR_RANGE, "T = %g must be positive and finite", (double)T);
+    // pass 1: copies per channel and the total
+    const double Td = (double)T;
+    long long extra = 0;
+    for (int j = 0; j < K; ++j) {
+        const float c = chmax_host[j];
+        if (!(c >= 0.0f) || std::isinf(c))
+            return fail(FQ_ERR_RANGE, "chmax[%d] = %g must be finite and >= 0", j, (double)c);
+        const double n = std::ceil((double)c / Td);
+        if (n > 1.0) extra += (long long)n - 1;
+        if (extra > (1LL << 30)) return fail(FQ_ERR_RANGE, "flattened width exceeds 2^30 channels");
+    }
+    const long long Kprime = (long long)K + extra;
+    const long long Kpad = (Kprime + align - 1) / align * align;
+    if (Kpad > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "padded width exceeds int32");
+    if (Kprime_out) *Kprime_out = (int)Kprime;
+    if (Kpad_out) *Kpad_out = (int)Kpad;
+    if (cap == 0) return FQ_OK;
+    if (!src_idx_host || !rep_host) return fail(FQ_ERR_NULL, "src_idx / rep is NULL with cap > 0");
+    if (cap < Kpad) return fail(FQ_ERR_SHAPE, "cap = %d < Kpad = %lld", cap, Kpad);
+    // pass 2: originals stay in place, extras go to the appended block in channel order
+    int tail = K;
+    for (int j = 0; j < K; ++j) {
+        double nd = std::ceil((double)chmax_host[j] / Td);
+        const int n = nd > 1.0 ? (int)nd : 1;
+        src_idx_host[j] = j;
+        rep_host[j] = n;
+        for (int e = 1; e < n; ++e, ++tail) {
+            src_idx_host[tail] = j;
+            rep_host[tail] = n;
+        }
+    }
+    for (; tail < (int)Kpad; ++tail) {
+        src_idx_host[tail] = -1;
+        rep_host[tail] = 0;
+    }
+    return FQ_OK;
+}
+
+size_t fq_act_workspace_bytes(int K, int Kpad)
+{
+    if (K <= 0 || Kpad <= 0) return 0;
+    return carve_act_workspace(nullptr, K, Kpad).bytes;
+}
+
+size_t fq_weights_workspace_bytes(int K, int Kpad) { return fq_act_workspace_bytes(K, Kpad); }
+
+size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits)
+{
+    if (M <= 0 || K <= 0 || Kpad <= 0 || (bits != 8 && bits != 4)) return 0;
+    const size_t xq = round_up((size_t)M * (bits == 8 ? (size_t)Kpad : (size_t)Kpad / 2), 256);
+    return xq + fq_act_workspace_bytes(K, Kpad);
+}
+
+int fq_flatten_weights(const void* W, int w_dtype, int N, int K, int ldw, const int32_t* src_idx, int Kpad,
+                       int bits, void* Wq_out, float* s_w_out, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    clear_error();
+    int rc = check_matrix("W", W, w_dtype, N, K, ldw);
+    if (rc) return rc;
+    rc = check_map(src_idx, Kpad, bits);
+    if (rc) return rc;
+    if (!Wq_out || !s_w_out || !workspace) return fail(FQ_ERR_NULL, "Wq_out, s_w_out or workspace is NULL");
+    if (!aligned16(Wq_out) || !aligned16(workspace)) return fail(FQ_ERR_ALIGN, "Wq_out or workspace is not 16-byte aligned");
+    if (workspace_bytes < fq_weights_workspace_bytes(K, Kpad))
+        return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
+                    fq_weights_workspace_bytes(K, Kpad));
+    ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
+    return launch_flatten_quant(W, w_dtype, N, K, ldw, src_idx, nullptr, Kpad, bits, /*mode=*/2, nullptr, Wq_out,
+                                s_w_out, ws, static_cast<hipStream_t>(stream));
+}
+
+int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx,
+                         const int32_t* rep, int Kpad, int bits, const float* absmax_in, void* Xq_out,
+                         float* s_x_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_matrix("X", X, x_dtype, M, K, ldx);
+    if (rc) return rc;
+    rc = check_map(src_idx, Kpad, bits);
+    if (rc) return rc;
+    if (!rep || !Xq_out || !s_x_out || !workspace) return fail(FQ_ERR_NULL, "rep, Xq_out, s_x_out or workspace is NULL");
+    if (!aligned16(Xq_out) || !aligned16(workspace)) return fail(FQ_ERR_ALIGN, "Xq_out or workspace is not 16-byte aligned");
+    if (workspace_bytes < fq_act_workspace_bytes(K, Kpad))
+        return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
+                    fq_act_workspace_bytes(K, Kpad));
+    ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
+    return launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in,
+                                Xq_out, s_x_out, ws, static_cast<hipStream_t>(stream));
+}
+
+int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+               void* Y, int y_dtype, int ldy, void* stream)
+{
+    clear_error();
+    int rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
+    if (rc) return rc;
+    return launch_gemm_int(Xq, Wq, M, N, Kpad, 8, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream));
+}
+
+int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+               void* Y, int y_dtype, int ldy, void* stream)
+{
+    clear_error();
+    int rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
+    if (rc) return rc;
+    return launch_gemm_int(Xq, Wq, M, N, Kpad, 4, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream));
+}
+
+int fq_linear(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx, const int32_t* rep,
+              int Kpad, const void* Wq, const float* s_w, int N, int bits, const float* absmax_in, void* Y,
+              int y_dtype, int ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_matrix("X", X, x_dtype, M, K, ldx);
+    if (rc) return rc;
+    rc = check_map(src_idx, Kpad, bits);
+    if (rc) return rc;
+    if (!rep || !workspace) return fail(FQ_ERR_NULL, "rep or workspace is NULL");
+    if (!aligned16(workspace)) return fail(FQ_ERR_ALIGN, "workspace is not 16-byte aligned");
+    if (workspace_bytes < fq_linear_workspace_bytes(M, K, Kpad, bits))
+        return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
+                    fq_linear_workspace_bytes(M, K, Kpad, bits));
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    const size_t xq_bytes = round_up((size_t)M * (bits == 8 ? (size_t)Kpad : (size_t)Kpad / 2), 256);
+    void* Xq = base;
+    ActWorkspace ws = carve_act_workspace(base + xq_bytes, K, Kpad);
+    float* s_x = ws.scalars + 1;
+    rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in, Xq,
+                              s_x, ws, st);
+    if (rc) return rc;
+    return launch_gemm_int(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy, st);
+}
+
+int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream)
+{
+    clear_error();
+    if (!X || !W || !Y) return fail(FQ_ERR_NULL, "X, W or Y is NULL");
+    if (M <= 0 || N <= 0 || K <= 0) return fail(FQ_ERR_SHAPE, "non-positive shape %d x %d x %d", M, N, K);
+    if (K % 8 != 0) return fail(FQ_ERR_SHAPE, "K = %d must be a multiple of 8", K);
+    if (ldy < N) return fail(FQ_ERR_SHAPE, "ldy = %d < N = %d", ldy, N);
+    if (!aligned16(X) || !aligned16(W)) return fail(FQ_ERR_ALIGN, "X or W is not 16-byte aligned");
+    return launch_gemm_bf16(X, W, M, N, K, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

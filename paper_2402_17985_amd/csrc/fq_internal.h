@@ -1,0 +1,51 @@
+// Internal declarations shared by the translation units of libfq (GPU library only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fq.h"
+
+namespace fq {
+
+// Records the reason of a failure for fq_last_error_string() and returns `code`.
+int fail(int code, const char* fmt, ...);
+void clear_error();
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int elem_size(int dtype)
+{
+    switch (dtype) {
+    case FQ_F32: return 4;
+    case FQ_F16: return 2;
+    case FQ_BF16: return 2;
+    case FQ_I32: return 4;
+    default: return 0;
+    }
+}
+
+// Workspace layout of the activation path: [cmax: K u32][mslot: Kpad f32][scalars: 4 f32]
+struct ActWorkspace {
+    uint32_t* cmax;   // per input channel max|x| as fp32 bit patterns
+    float* mslot;     // per flattened slot multiplier m_p
+    float* scalars;   // [0] = a'
+    size_t bytes;
+};
+ActWorkspace carve_act_workspace(void* base, int K, int Kpad);
+
+// ---- launchers (each validates nothing: the C-ABI layer has already done so) ----
+// mode 0: activation, dynamic absmax; 1: activation, static absmax (*absmax_in); 2: weights
+int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld,
+                         const int32_t* src_idx, const int32_t* rep, int Kpad, int bits,
+                         int mode, const float* absmax_in, void* out, float* scale_out,
+                         const ActWorkspace& ws, hipStream_t stream);
+
+int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits,
+                    const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
+                    hipStream_t stream);
+
+int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy,
+                     hipStream_t stream);
+
+}  // namespace fq

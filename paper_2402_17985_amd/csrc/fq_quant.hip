@@ -1,0 +1,335 @@
+// Flatten + per-tensor quantize kernels (activation path at inference time, weight path offline).
+//
+// arXiv 2402.17985: Sec. 4.1 Eq. 3 (flatten, equal-split form: each of the n copies of a
+// channel holds x/n), Eq. 4 (weight channel repeated), Sec. 2.1 Eq. 1 (per-tensor scale
+// s = max|.| / qmax, round, here round-half-even, then clamp).
+//
+// Three kernels, all bandwidth bound:
+//   colabsmax      per input channel max|x| over the rows (64-wide wave reads 1 KiB of a row per
+//                  instruction; per-thread running max; one atomic max per column per block;
+//                  the max of non-negative floats is taken on their bit patterns, so the result
+//                  does not depend on the order of the updates)
+//   scale          one workgroup: per-tensor absmax a' by wavefront reductions, the scale s, and
+//                  the per-slot multiplier m_p = fl32(qmax / (n_p * a')) (float64 quotient)
+//   flatten_quant  each thread owns 16 consecutive flattened slots for a strip of rows: the map
+//                  and multipliers are read once into registers, then per row 16 values are
+//                  read (one contiguous 32/64-byte vector read when the slots are an identity
+//                  run, else a gather that hits the cache lines the neighbours just read),
+//                  multiplied, rounded, clamped, packed and stored as one 16-byte (INT8) or
+//                  8-byte (INT4) write.
+#include "fq_internal.h"
+
+namespace fq {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+
+template <int DT> struct Elem;
+template <> struct Elem<FQ_F32> {
+    typedef float type;
+    static constexpr int VEC = 4;   // elements per 16 bytes
+    static __device__ __forceinline__ float widen(float v) { return v; }
+};
+template <> struct Elem<FQ_F16> {
+    typedef _Float16 type;
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float widen(_Float16 v) { return (float)v; }
+};
+template <> struct Elem<FQ_BF16> {
+    typedef uint16_t type;
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+};
+
+// Widen one 16-byte vector of storage elements to floats.
+template <int DT> __device__ __forceinline__ void widen16(const v4u raw, float* out);
+template <> __device__ __forceinline__ void widen16<FQ_F32>(const v4u raw, float* out)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(raw[i]);
+}
+template <> __device__ __forceinline__ void widen16<FQ_BF16>(const v4u raw, float* out)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(raw[i] << 16);
+        out[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+    }
+}
+template <> __device__ __forceinline__ void widen16<FQ_F16>(const v4u raw, float* out)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        union { uint32_t u; _Float16 h[2]; } cv;
+        cv.u = raw[i];
+        out[2 * i] = (float)cv.h[0];
+        out[2 * i + 1] = (float)cv.h[1];
+    }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, int count, uint32_t v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per input channel absmax
+// ---------------------------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void colabsmax_kernel(const void* __restrict__ Xv, int M, int K, int ld,
+                                                        int rows_per_block, uint32_t* __restrict__ cmax)
+{
+    typedef typename Elem<DT>::type T;
+    constexpr int VEC = Elem<DT>::VEC;
+    const T* X = static_cast<const T*>(Xv);
+    const int col0 = (blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (col0 >= K) return;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(M, r0 + rows_per_block);
+    float mx[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) mx[v] = 0.0f;
+    if (col0 + VEC <= K) {
+        const T* p = X + (size_t)r0 * ld + col0;
+#pragma unroll 4
+        for (int r = r0; r < r1; ++r, p += ld) {
+            v4u raw = *reinterpret_cast<const v4u*>(p);
+            float f[VEC];
+            widen16<DT>(raw, f);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) mx[v] = fmaxf(mx[v], fabsf(f[v]));
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) atomicMax(&cmax[col0 + v], __float_as_uint(mx[v]));
+    } else {
+        for (int v = 0; col0 + v < K; ++v) {
+            float m = 0.0f;
+            for (int r = r0; r < r1; ++r) m = fmaxf(m, fabsf(Elem<DT>::widen(X[(size_t)r * ld + col0 + v])));
+            atomicMax(&cmax[col0 + v], __float_as_uint(m));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-tensor absmax, scale and per-slot multipliers (one workgroup)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict__ cmax, int K,
+                                                     const int32_t* __restrict__ src,
+                                                     const int32_t* __restrict__ rep, int Kpad, int qmax,
+                                                     int mode, const float* __restrict__ absmax_in,
+                                                     float* __restrict__ mslot, float* __restrict__ scale_out,
+                                                     float* __restrict__ scalars)
+{
+    __shared__ float red[16];
+    __shared__ float a_shared;
+    const int tid = threadIdx.x;
+    float a = 0.0f;
+    if (mode == 0) {
+        // a' = max over slots of fl32(cmax[src] / n); the float64 quotient rounded to fp32 is the
+        // correctly rounded fp32 quotient (53 >= 2*24 + 2 bits)
+        for (int p = tid; p < Kpad; p += 1024) {
+            int s = src[p], n = rep[p];
+            if ((unsigned)s < (unsigned)K && n > 0)
+                a = fmaxf(a, (float)((double)__uint_as_float(cmax[s]) / (double)n));
+        }
+    } else if (mode == 2) {
+        for (int j = tid; j < K; j += 1024) a = fmaxf(a, __uint_as_float(cmax[j]));
+    }
+    if (mode != 1) {
+        a = wave_max(a);
+        if ((tid & 63) == 0) red[tid >> 6] = a;
+        __syncthreads();
+        if (tid < 64) {
+            float t = (tid < 16) ? red[tid] : 0.0f;
+            t = wave_max(t);
+            if (tid == 0) a_shared = t;
+        }
+        __syncthreads();
+        a = a_shared;
+    } else {
+        a = *absmax_in;
+        if (!(a >= 0.0f) || a > 3.0e38f) a = 0.0f;     // negative / NaN / Inf static bound: treated as 0
+    }
+    const double ad = (double)a;
+    if (tid == 0) {
+        *scale_out = (a == 0.0f) ? 1.0f : (float)(ad / (double)qmax);
+        scalars[0] = a;
+    }
+    for (int p = tid; p < Kpad; p += 1024) {
+        int s = src[p];
+        int n = (mode == 2) ? 1 : rep[p];
+        bool valid = (unsigned)s < (unsigned)K && n > 0 && a != 0.0f;
+        mslot[p] = valid ? (float)((double)qmax / ((double)n * ad)) : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// flatten + quantize
+// ---------------------------------------------------------------------------------------------
+template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
+{
+    constexpr float hi = (float)((1 << (BITS - 1)) - 1);
+    constexpr float lo = -(float)(1 << (BITS - 1));
+    float r = rintf(x * m);                 // one fp32 multiply, then round-half-even
+    r = fminf(fmaxf(r, lo), hi);
+    return (int)r;
+}
+
+template <int DT, int BITS>
+__global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restrict__ Xv, int M, int K, int ld,
+                                                            const int32_t* __restrict__ src,
+                                                            const float* __restrict__ mslot, int Kpad,
+                                                            int rows_per_thread, uint8_t* __restrict__ out)
+{
+    typedef typename Elem<DT>::type T;
+    constexpr int VEC = Elem<DT>::VEC;
+    const T* X = static_cast<const T*>(Xv);
+    const int G = Kpad >> 4;                                   // groups of 16 slots per row
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int g = (int)(gid % G);
+    const long long rt = gid / G;
+    const long long r0l = rt * rows_per_thread;
+    if (r0l >= M) return;
+    const int r0 = (int)r0l;
+    const int r1 = min(M, r0 + rows_per_thread);
+    const int p0 = g << 4;
+
+    int s[16];
+    float m[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v4i sv = *reinterpret_cast<const v4i*>(src + p0 + 4 * i);
+        v4f mv = *reinterpret_cast<const v4f*>(mslot + p0 + 4 * i);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { s[4 * i + j] = sv[j]; m[4 * i + j] = mv[j]; }
+    }
+    bool contig = (s[0] >= 0) && (s[0] % VEC == 0) && (s[0] + 15 < K);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if ((unsigned)s[i] >= (unsigned)K) { s[i] = 0; m[i] = 0.0f; contig = false; }   // padding / invalid
+        if (s[i] != s[0] + i) contig = false;
+    }
+
+    const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
+    uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
+    const T* row = X + (size_t)r0 * ld;
+
+#pragma unroll 2
+    for (int r = r0; r < r1; ++r, row += ld, o += orow_bytes) {
+        float x[16];
+        if (contig) {
+            const v4u* vp = reinterpret_cast<const v4u*>(row + s[0]);
+#pragma unroll
+            for (int i = 0; i < 16 / VEC; ++i) {
+                v4u raw = vp[i];
+                widen16<DT>(raw, x + i * VEC);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = Elem<DT>::widen(row[s[i]]);
+        }
+        int q[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(x[i], m[i]);
+        if (BITS == 8) {
+            v4u w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
+                       ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
+            *reinterpret_cast<v4u*>(o) = w;
+        } else {
+            v2u w;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint32_t acc = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc |= (uint32_t)(q[8 * i + j] & 0xf) << (4 * j);
+                w[i] = acc;
+            }
+            *reinterpret_cast<v2u*>(o) = w;
+        }
+    }
+}
+
+template <int DT>
+int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx, const int32_t* rep,
+                     int Kpad, int bits, int mode, const float* absmax_in, void* out, float* scale_out,
+                     const ActWorkspace& ws, hipStream_t stream)
+{
+    constexpr int VEC = Elem<DT>::VEC;
+    const int qmax = (1 << (bits - 1)) - 1;
+    if (mode != 1) {
+        fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(ws.cmax, K, 0u);
+        const int bx = (K + 256 * VEC - 1) / (256 * VEC);
+        // aim at about 2048 workgroups; between 8 and 256 rows each
+        long long rpb = ((long long)M * bx + 2047) / 2048;
+        if (rpb < 8) rpb = 8;
+        if (rpb > 256) rpb = 256;
+        dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
+        colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, ws.cmax);
+    }
+    scale_kernel<<<1, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
+                                         scale_out, ws.scalars);
+    const int G = Kpad / 16;
+    // rows per thread: as many as 16 while the launch still has >= 2048 waves
+    int rpt = 16;
+    while (rpt > 1 && ((long long)G * ((M + rpt - 1) / rpt)) < 2048LL * 64) rpt >>= 1;
+    const long long threads = (long long)G * ((M + rpt - 1) / rpt);
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (bits == 8)
+        flatten_quant_kernel<DT, 8><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt,
+                                                                static_cast<uint8_t*>(out));
+    else
+        flatten_quant_kernel<DT, 4><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt,
+                                                                static_cast<uint8_t*>(out));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "flatten-quantize launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
+}
+
+}  // namespace
+
+ActWorkspace carve_act_workspace(void* base, int K, int Kpad)
+{
+    ActWorkspace ws;
+    uint8_t* p = static_cast<uint8_t*>(base);
+    size_t off = 0;
+    ws.cmax = reinterpret_cast<uint32_t*>(p + off);
+    off += round_up((size_t)K * 4, 256);
+    ws.mslot = reinterpret_cast<float*>(p + off);
+    off += round_up((size_t)Kpad * 4, 256);
+    ws.scalars = reinterpret_cast<float*>(p + off);
+    off += 256;
+    ws.bytes = off;
+    return ws;
+}
+
+int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld, const int32_t* src_idx,
+                         const int32_t* rep, int Kpad, int bits, int mode, const float* absmax_in,
+                         void* out, float* scale_out, const ActWorkspace& ws, hipStream_t stream)
+{
+    switch (x_dtype) {
+    case FQ_F32:
+        return launch_for_dtype<FQ_F32>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+    case FQ_F16:
+        return launch_for_dtype<FQ_F16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+    case FQ_BF16:
+        return launch_for_dtype<FQ_BF16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+    default:
+        return fail(FQ_ERR_DTYPE, "unsupported input dtype %d", x_dtype);
+    }
+}
+
+}  // namespace fq

@@ -1,0 +1,260 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars (arXiv 2402.17985 fixes the arithmetic; the tolerances follow from it):
+  - flatten maps, quantized INT8 / packed INT4 tensors, scales and int32 accumulators: bit-exact;
+  - dequantized outputs against the oracle's float64 y = acc * s_x * s_w:
+      fp32 out  <= 1e-6 relative  (fl32(acc), fl32(s_x*s_w) and one multiply: 3 roundings of 2^-24),
+      fp16 out  <= 1e-3 relative  (half ulp 4.9e-4 on top of the above),
+      bf16 out  <= 2^-8 relative  (bf16 keeps 8 significand bits: its own rounding is up to 2^-9;
+                 the fp32 value before that rounding is held to 1e-6 by the fp32 case).
+"""
+import numpy as np
+import pytest
+import torch
+
+import fq_workloads as WL
+import paper_2402_17985_amd as fq
+from oracle import fq_oracle as O
+from tests.gpu_util import DEV, bf16_to_f64, bytes_ws, dev_i32, rel_err, scalar, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer(cfg, idx=0, **over):
+    return WL.make_layer(WL.CONFIGS[cfg], idx, **over)
+
+
+def _gpu_flatten_quant(L, src, rep, bits, a_static=None, X_dev=None):
+    M, K = L.X.shape
+    Kpad = len(src)
+    Xd = to_dev(L.X_store, L.spec.x_dtype) if X_dev is None else X_dev
+    out = torch.full((M, Kpad if bits == 8 else Kpad // 2), 0x55, dtype=torch.uint8, device=DEV)
+    s_x = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = bytes_ws(fq.fq_act_workspace_bytes(K, Kpad))
+    fq.fq_flatten_quant_act(Xd, dev_i32(src), dev_i32(rep), bits, out, s_x, ws,
+                            absmax_in=None if a_static is None else scalar(a_static))
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), np.float32(s_x.item())
+
+
+def _oracle_flatten_quant(L, src, rep, bits, a_static=None):
+    a = O.act_absmax_dynamic(L.X, src, rep) if a_static is None else np.float32(a_static)
+    q, s_x = O.flatten_quant_act(L.X, src, rep, bits, a)
+    return (q.view(np.uint8) if bits == 8 else O.pack_i4(q)), s_x
+
+
+# ------------------------------------------------------------------------------------------
+# flatten + quantize (activations)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("cfg,over", [
+    ("cfg1", {}), ("cfg1b", {}),
+    ("cfg2", dict(M_override=333, K_override=1000, N_override=8)),        # ragged M, K not a multiple of 16
+    ("cfg3", dict(M_override=517, K_override=2048, N_override=8)),
+    ("cfg4", dict(M_override=70, K_override=5120, N_override=8)),
+])
+def test_flatten_quant_act_dynamic(cfg, over, bits):
+    L = _layer(cfg, **over)
+    if L.spec.x_dtype != "f32" and L.X.shape[1] % 8:
+        pytest.skip("row stride must be a multiple of 16 bytes")
+    src, rep, kp, kpad = fq.fq_flatten_plan(L.chmax, L.T)
+    osrc, orep, okp, okpad = O.plan(L.chmax, L.T)
+    assert (kp, kpad) == (okp, okpad) and (src == osrc).all() and (rep == orep).all()
+    got, s_x = _gpu_flatten_quant(L, src, rep, bits)
+    want, s_x_o = _oracle_flatten_quant(L, src, rep, bits)
+    assert s_x == s_x_o
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_flatten_quant_act_static_clamps_and_dtypes(bits, dtype):
+    """The paper's static mode with a' = T; chmax is deliberately understated for two channels so
+    that values beyond the calibrated range reach the clamp."""
+    rng = np.random.default_rng(11)
+    M, K = 129, 264
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    X[:, [5, 77, 200]] *= np.array([30, 12, 55], np.float32)
+    store, Xf = WL.round_to_dtype(X, dtype)
+    chmax = np.abs(Xf).max(axis=0)
+    chmax[[5, 100]] *= 0.5
+    T = 2.0
+    src, rep, kp, kpad = fq.fq_flatten_plan(chmax, T)
+    L = WL.Layer(WL.LayerSpec("s", M, K, 8, bits, dtype, dtype), store, Xf, None, None, chmax, T)
+    got, s_x = _gpu_flatten_quant(L, src, rep, bits, a_static=T)
+    want, s_x_o = _oracle_flatten_quant(L, src, rep, bits, a_static=T)
+    assert s_x == s_x_o and np.array_equal(got, want)
+    q = want.view(np.int8) if bits == 8 else O.unpack_i4(want)
+    assert q.min() == -(1 << (bits - 1))                     # the clamp is live
+
+
+def test_flatten_quant_act_strided_rows_zero_input_and_bad_map():
+    rng = np.random.default_rng(3)
+    M, K, ld = 40, 96, 128
+    buf = torch.zeros((M, ld), dtype=torch.float32, device=DEV)
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    X[:, 9] *= 25
+    buf[:, :K] = torch.from_numpy(X).to(DEV)
+    chmax = np.abs(X).max(axis=0)
+    src, rep, kp, kpad = fq.fq_flatten_plan(chmax, 3.0)
+    L = WL.Layer(WL.LayerSpec("s", M, K, 8, 8, "f32", "f32"), X, X, None, None, chmax, 3.0)
+    got, s_x = _gpu_flatten_quant(L, src, rep, 8, X_dev=buf[:, :K])
+    want, s_x_o = _oracle_flatten_quant(L, src, rep, 8)
+    assert s_x == s_x_o and np.array_equal(got, want)
+    # all-zero activations: zeros out, s_x = 1
+    Lz = WL.Layer(L.spec, np.zeros_like(X), np.zeros_like(X), None, None, chmax, 3.0)
+    got, s_x = _gpu_flatten_quant(Lz, src, rep, 8)
+    assert s_x == np.float32(1.0) and not got.any()
+    # a map with out-of-range sources: those slots read as padding, nothing faults
+    bad = src.copy()
+    bad[3] = K + 1000
+    bad[kp - 1] = -7
+    got, _ = _gpu_flatten_quant(L, bad, rep, 8)
+    good = src.copy()
+    good[3] = -1
+    good[kp - 1] = -1
+    want, _ = _oracle_flatten_quant(L, good, rep, 8)
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------------------------------
+# weights (offline)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("cfg,over", [("cfg1b", {}), ("cfg2", dict(M_override=64, K_override=1024, N_override=301))])
+def test_flatten_weights(cfg, over, bits):
+    L = _layer(cfg, **over)
+    src, rep, kp, kpad = fq.fq_flatten_plan(L.chmax, L.T)
+    Wd = to_dev(L.W_store, L.spec.w_dtype)
+    lay = fq.FqLinear(Wd, L.chmax, L.T, bits)
+    torch.cuda.synchronize()
+    Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
+    want = Wq_o.view(np.uint8) if bits == 8 else O.pack_i4(Wq_o)
+    assert np.float32(lay.s_w.item()) == s_w_o
+    assert np.array_equal(lay.Wq.cpu().numpy().view(np.uint8), want)
+
+
+# ------------------------------------------------------------------------------------------
+# integer GEMM: raw accumulators, every tile variant, ragged shapes
+# ------------------------------------------------------------------------------------------
+def _rand_q(rng, rows, Kpad, bits):
+    lo, hi = -(1 << (bits - 1)), (1 << (bits - 1))
+    return rng.integers(lo, hi, (rows, Kpad), dtype=np.int8)
+
+
+def _gemm_acc(Xq, Wq, bits):
+    M, N = Xq.shape[0], Wq.shape[0]
+    Y = torch.full((M, N), -12345, dtype=torch.int32, device=DEV)
+    if bits == 8:
+        fq.fq_gemm_i8(torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV), None, None, Y)
+    else:
+        fq.fq_gemm_i4(torch.from_numpy(O.pack_i4(Xq)).to(DEV), torch.from_numpy(O.pack_i4(Wq)).to(DEV), None, None, Y)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_accumulators_bit_exact(variant, bits):
+    rng = np.random.default_rng(100 * variant + bits)
+    fq.fq_gemm_select(variant)
+    try:
+        # several tiles + ragged tails in M and N; Kpad = 32 mod 64 / 128 exercises the masked last k-stage
+        for (M, N, Kpad) in [(300, 520, 416), (257, 129, 1056), (1, 1, 32), (33, 700, 160)]:
+            Xq, Wq = _rand_q(rng, M, Kpad, bits), _rand_q(rng, N, Kpad, bits)
+            got = _gemm_acc(Xq, Wq, bits)
+            assert np.array_equal(got, O.gemm_i32(Xq, Wq)), (variant, bits, M, N, Kpad)
+    finally:
+        fq.fq_gemm_select(-1)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_extreme_values_do_not_wrap(bits):
+    Kpad, lo = 26016, -(1 << (bits - 1))
+    Xq = np.full((40, Kpad), lo, np.int8)
+    Wq = np.full((70, Kpad), lo, np.int8)
+    Wq[1::2] = -lo - 1
+    got = _gemm_acc(Xq, Wq, bits)
+    assert np.array_equal(got, O.gemm_i32(Xq, Wq))
+    assert got[0, 0] == Kpad * lo * lo
+
+
+@pytest.mark.parametrize("ydt,tol", [(torch.float32, 1e-6), (torch.float16, 1e-3), (torch.bfloat16, 2.0 ** -8)])
+def test_gemm_dequant_epilogue(ydt, tol):
+    rng = np.random.default_rng(5)
+    M, N, Kpad = 200, 333, 512
+    Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
+    s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+    ldy = 336
+    Ybuf = torch.full((M, ldy), 7.0, dtype=ydt, device=DEV)
+    fq.fq_gemm_i8(torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV), scalar(s_x), scalar(s_w), Ybuf[:, :N])
+    torch.cuda.synchronize()
+    ref = O.dequant(O.gemm_i32(Xq, Wq), s_x, s_w)
+    got = Ybuf[:, :N].float().cpu().numpy().astype(np.float64)
+    assert rel_err(got, ref).max() <= tol
+    assert (Ybuf[:, N:].float() == 7.0).all()                # nothing written beyond column N
+
+
+# ------------------------------------------------------------------------------------------
+# the whole layer
+# ------------------------------------------------------------------------------------------
+def _run_linear(L, bits, ydt, a_static=None):
+    Wd = to_dev(L.W_store, L.spec.w_dtype)
+    lay = fq.FqLinear(Wd, L.chmax, L.T, bits)
+    Xd = to_dev(L.X_store, L.spec.x_dtype)
+    Y = lay.forward(Xd, out_dtype=ydt, absmax_in=None if a_static is None else scalar(a_static))
+    torch.cuda.synchronize()
+    return lay, Y
+
+
+@pytest.mark.parametrize("cfg,over,bits", [
+    ("cfg1", {}, 8), ("cfg1b", {}, 8), ("cfg1b", {}, 4),
+    ("cfg2", dict(M_override=300, K_override=1024, N_override=520), 8),
+    ("cfg3", dict(M_override=384, K_override=1024, N_override=700), 4),
+    ("cfg4", dict(M_override=260, K_override=2048, N_override=264), 4),
+])
+def test_linear_end_to_end(cfg, over, bits):
+    L = _layer(cfg, **over)
+    src, rep, kp, kpad = O.plan(L.chmax, L.T)
+    Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
+    acc_o, y_o, s_x_o = O.linear(L.X, src, rep, Wq_o, s_w_o, bits)
+    lay, acc = _run_linear(L, bits, torch.int32)
+    assert np.array_equal(acc.cpu().numpy(), acc_o)
+    _, y32 = _run_linear(L, bits, torch.float32)
+    assert rel_err(y32.cpu().numpy().astype(np.float64), y_o).max() <= 1e-6
+    _, y16 = _run_linear(L, bits, torch.bfloat16)
+    assert rel_err(bf16_to_f64(y16), y_o).max() <= 2.0 ** -8
+    # static mode (the paper's): a' = T
+    acc_s, _, _ = O.linear(L.X, src, rep, Wq_o, s_w_o, bits, a_static=L.T)
+    _, acc_sg = _run_linear(L, bits, torch.int32, a_static=L.T)
+    assert np.array_equal(acc_sg.cpu().numpy(), acc_s)
+
+
+def test_linear_is_deterministic():
+    L = _layer("cfg2", M_override=512, K_override=1024, N_override=512)
+    lay, a = _run_linear(L, 8, torch.bfloat16)
+    Xd = to_dev(L.X_store, L.spec.x_dtype)
+    b = lay.forward(Xd, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ------------------------------------------------------------------------------------------
+# bf16 baseline GEMM
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", [0, 2])
+def test_gemm_bf16_baseline(variant):
+    rng = np.random.default_rng(9)
+    M, N, K = 300, 260, 1032
+    Xs, Xf = WL.round_to_dtype(rng.standard_normal((M, K), dtype=np.float32), "bf16")
+    Ws, Wf = WL.round_to_dtype(rng.standard_normal((N, K), dtype=np.float32) / np.float32(np.sqrt(K)), "bf16")
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    fq.fq_gemm_select(variant)
+    try:
+        fq.fq_gemm_bf16(to_dev(Xs, "bf16"), to_dev(Ws, "bf16"), Y)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_gemm_select(-1)
+    ref = Xf.astype(np.float64) @ Wf.astype(np.float64).T
+    # fp32 accumulation of K = 1032 products, then one bf16 rounding
+    assert rel_err(bf16_to_f64(Y), ref).max() <= 2.0 ** -8 + 1e-4
