@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlattenQuant linear-layer hot path on one MI355X.
+
+Workload (default): the metric's "M = 8192 LLaMA-7B shapes" — the INT4 FFN pair 4096->11008 and
+11008->4096 plus the INT8 4096->4096 projection, all at M = 8192 tokens, synthetic outlier-bearing
+bf16 activations (fq_workloads.py).  One step = one fq_linear call per layer: dynamic per-tensor
+absmax, fused flatten-quantize, integer MFMA GEMM with the dequantize epilogue (bf16 out).
+Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-step throughput in TOPS (integer ops actually executed,
+2*M*Kpad*N per layer), the roofline of the dominant kernel (the INT4 GEMM) from HIP-event timings
+taken in this process, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (INT4 is widened to int8 on chip: same ceiling)
+BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def event_time_ms(torch, fn, iters, warmup=2):
+    """Average duration of fn() over `iters` launches, HIP events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--configs", default="cfg3,cfg3i8", help="comma-separated workload names from fq_workloads")
+    ap.add_argument("--variant", type=int, default=-1, help="force a GEMM tile variant (fq_gemm_select)")
+    ap.add_argument("--static", action="store_true", help="static activation scale a' = T (the paper's mode)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--sweep", action="store_true", help="also time every GEMM variant per layer (stderr table)")
+    ap.add_argument("--kernels-only", action="store_true", help="skip the per-kernel breakdown of bf16 / flatten")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import fq_workloads as WL
+    import paper_2402_17985_amd as fq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    fq.lib()
+    dev = "cuda:0"
+    fq.fq_gemm_select(args.variant)
+
+    # ---------------- build the layers (offline part: plan + weight quantization) ----------------
+    layers = []
+    for cname in args.configs.split(","):
+        cfg = WL.CONFIGS[cname]
+        for li in range(len(cfg.layers)):
+            t0 = time.time()
+            L = WL.make_layer(cfg, li)
+            sp = L.spec
+            Xd = torch.from_numpy(L.X_store.view(np.int16)).to(dev).view(torch.bfloat16)
+            Wd = torch.from_numpy(L.W_store.view(np.int16)).to(dev).view(torch.bfloat16)
+            lay = fq.FqLinear(Wd, L.chmax, L.T, sp.bits, device=dev)
+            Y = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
+            Ybf = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
+            a_static = torch.tensor([L.T], dtype=torch.float32, device=dev) if args.static else None
+            lay.workspace(sp.M)
+            layers.append(dict(name=f"{cname}.{sp.name}", spec=sp, L=L, X=Xd, W=Wd, lay=lay, Y=Y, Ybf=Ybf,
+                               a_static=a_static))
+            log(f"[setup] {cname}.{sp.name}: M={sp.M} K={sp.K} N={sp.N} bits={sp.bits} T={L.T:.4g} "
+                f"Kprime={lay.Kprime} Kpad={lay.Kpad} (+{100.0 * (lay.Kpad - sp.K) / sp.K:.1f}%) "
+                f"max n={int(lay.rep_host.max())} [{time.time() - t0:.1f}s]")
+    torch.cuda.synchronize()
+
+    def step():
+        for d in layers:
+            d["lay"].forward(d["X"], Y=d["Y"], absmax_in=d["a_static"])
+
+    # ---------------- the timed region: W warm-up steps, then exactly K steps ----------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ops_hw = sum(2.0 * d["spec"].M * d["lay"].Kpad * d["spec"].N for d in layers)
+    ops_eff = sum(2.0 * d["spec"].M * d["spec"].K * d["spec"].N for d in layers)
+    value = ops_hw / (t_step_ms * 1e-3) / 1e12
+
+    # ---------------- per-kernel breakdown (HIP events, same process) ----------------
+    rows = []
+    t_bf16_total = 0.0
+    dom = dict(flops=0.0, ms=0.0, launches=0)       # the dominant kernel: INT4 GEMM (else INT8)
+    dom_bits = 4 if any(d["spec"].bits == 4 for d in layers) else 8
+    fqa = dict(bytes=0.0, ms=0.0)
+    for d in layers:
+        sp, lay = d["spec"], d["lay"]
+        Kpad = lay.Kpad
+        cols = Kpad if sp.bits == 8 else Kpad // 2
+        Xq = torch.empty((sp.M, cols), dtype=torch.int8 if sp.bits == 8 else torch.uint8, device=dev)
+        s_x = torch.empty(1, dtype=torch.float32, device=dev)
+        ws = torch.empty(fq.fq_act_workspace_bytes(sp.K, Kpad), dtype=torch.uint8, device=dev)
+        f_act = lambda: fq.fq_flatten_quant_act(d["X"], lay.src, lay.rep, sp.bits, Xq, s_x, ws, absmax_in=d["a_static"])
+        gemm = fq.fq_gemm_i8 if sp.bits == 8 else fq.fq_gemm_i4
+        f_gemm = lambda: gemm(Xq, lay.Wq, s_x, lay.s_w, d["Y"])
+        f_lin = lambda: lay.forward(d["X"], Y=d["Y"], absmax_in=d["a_static"])
+        f_bf = lambda: fq.fq_gemm_bf16(d["X"], d["W"], d["Ybf"])
+        t_act = event_time_ms(torch, f_act, args.steps)
+        t_gemm = event_time_ms(torch, f_gemm, args.steps)
+        t_lin = event_time_ms(torch, f_lin, args.steps)
+        t_bf = event_time_ms(torch, f_bf, args.steps)
+        t_bf16_total += t_bf
+        flops = 2.0 * sp.M * Kpad * sp.N
+        # algorithmic HBM bytes of flatten-quantize: X read once (static) or twice (dynamic), Xq written
+        act_bytes = sp.M * sp.K * 2 * (1 if args.static else 2) + sp.M * cols
+        if sp.bits == dom_bits:
+            dom["flops"] += flops
+            dom["ms"] += t_gemm
+            dom["launches"] += 1
+        fqa["bytes"] += act_bytes
+        fqa["ms"] += t_act
+        row = dict(layer=d["name"], bits=sp.bits, M=sp.M, K=sp.K, N=sp.N, Kpad=Kpad,
+                   ms_flatten_quant=round(t_act, 4), ms_gemm=round(t_gemm, 4), ms_linear=round(t_lin, 4),
+                   ms_gemm_bf16=round(t_bf, 4),
+                   gemm_tops=round(flops / t_gemm / 1e9, 1),
+                   gemm_pct_int8_peak=round(100 * flops / t_gemm / 1e9 / INT8_PEAK_TOPS, 2),
+                   bf16_tflops=round(2.0 * sp.M * sp.K * sp.N / t_bf / 1e9, 1),
+                   flatten_quant_gbs=round(act_bytes / t_act / 1e6, 1),
+                   linear_eff_tops=round(2.0 * sp.M * sp.K * sp.N / t_lin / 1e9, 1),
+                   speedup_vs_bf16=round(t_bf / t_lin, 3))
+        rows.append(row)
+        log("[kernel] " + json.dumps(row))
+        if args.sweep:
+            for v in range(4):
+                fq.fq_gemm_select(v)
+                tg = event_time_ms(torch, f_gemm, max(5, args.steps // 2))
+                tb = event_time_ms(torch, f_bf, max(5, args.steps // 2))
+                log(f"[sweep] {d['name']} variant {v}: int{sp.bits} gemm {tg:.4f} ms = {flops / tg / 1e9:.0f} TOPS; "
+                    f"bf16 {tb:.4f} ms = {2.0 * sp.M * sp.K * sp.N / tb / 1e9:.0f} TFLOPS")
+            fq.fq_gemm_select(args.variant)
+        del Xq, ws
+    dom_avg_ms = dom["ms"] / dom["launches"]
+    dom_achieved = dom["flops"] / dom["launches"] / dom_avg_ms / 1e9          # TOPS
+    roofline = dict(bound="mfma", kernel=f"gemm_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
+                    peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4), traffic=None,
+                    avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])
+    flatten_roofline = dict(bound="hbm", kernel="colabsmax + scale + flatten_quant", achieved=round(fqa["bytes"] / fqa["ms"] / 1e6, 1),
+                            peak=HBM_PEAK_GBS, unit="GB/s", frac=round(fqa["bytes"] / fqa["ms"] / 1e6 / HBM_PEAK_GBS, 4))
+
+    # ---------------- CPU oracle on a bounded sample ----------------
+    cpu = None
+    if not args.no_cpu:
+        from oracle import fq_oracle as O
+        d = max(layers, key=lambda d: d["spec"].M * d["lay"].Kpad * d["spec"].N)
+        L, sp, lay = d["L"], d["spec"], d["lay"]
+        Wq_o, s_w_o = O.flatten_weights(L.W, lay.src_host, sp.bits)      # offline part, not timed
+        sample_rows = 16
+        t0 = time.perf_counter()
+        O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=sample_rows)
+        dt = time.perf_counter() - t0
+        # size the sample for roughly 15 s of oracle time
+        sample_rows = int(min(sp.M, max(16, sample_rows * 15.0 / max(dt, 1e-3))))
+        t0 = time.perf_counter()
+        acc_o, y_o, _ = O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=sample_rows)
+        dt = time.perf_counter() - t0
+        cpu_tops = 2.0 * sample_rows * lay.Kpad * sp.N / dt / 1e12
+        cpu = dict(value=round(cpu_tops, 5), unit="TOPS", cores=O.num_threads(), kind="oracle",
+                   sample=f"fq_linear (dynamic absmax over all {sp.M} rows, flatten-quantize + INT{sp.bits} GEMM + dequant) "
+                          f"on the first {sample_rows} of {sp.M} token rows of {d['name']} "
+                          f"(K={sp.K}, Kpad={lay.Kpad}, N={sp.N}); {dt:.1f} s")
+        # the sample doubles as a check of the timed configuration
+        got = torch.empty((sp.M, sp.N), dtype=torch.int32, device=dev)
+        lay.forward(d["X"], Y=got)
+        torch.cuda.synchronize()
+        same = bool(np.array_equal(got[:sample_rows].cpu().numpy(), acc_o))
+        log(f"[check] GPU accumulators equal the oracle's on the {sample_rows}-row sample: {same}")
+        if not same:
+            sys.exit("bench.py: GPU result differs from the oracle on the sampled rows")
+
+    out = {
+        "metric": "fq_linear_tops_m8192_llama7b_shapes",
+        "value": round(value, 2),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(t_step_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4+int8 (int8 MFMA, int32 accumulate; bf16 in/out)",
+        "data": "synthetic",
+        "config": {"workload": "+".join(args.configs.split(",")) +
+                               ": LLaMA-7B FFN pair 4096->11008->4096 INT4 and 4096->4096 INT8 projection, M=8192 tokens, "
+                               "bf16 activations with 0.5% outlier channels x[10,100], <=15% of channels flattened",
+                   "activation_scale": "static a'=T" if args.static else "dynamic per-tensor absmax",
+                   "layers": [r["layer"] for r in rows], "gemm_variant": args.variant},
+        "pct_int8_mfma_peak": round(100.0 * value / INT8_PEAK_TOPS, 2),
+        "effective_tops": round(ops_eff / (t_step_ms * 1e-3) / 1e12, 2),
+        "speedup_vs_bf16": round(t_bf16_total / t_step_ms, 3),
+        "ms_bf16_gemm_same_shapes": round(t_bf16_total, 4),
+        "roofline": roofline,
+        "flatten_quant_roofline": flatten_roofline,
+        "cpu_baseline": cpu,
+        "layers": rows,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

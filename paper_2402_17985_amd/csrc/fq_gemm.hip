@@ -1,5 +1,5 @@
 // LDS-tiled MFMA GEMMs for gfx950: INT8, packed INT4 (widened to INT8 in registers) and the
-// bf16 baseline, one kernel template.
+// bf16 baseline, from one kernel template.
 //
 // arXiv 2402.17985 Sec. 5.1: the quantized linear layer is an INT8 / INT4 GEMM with int32
 // accumulation whose result is scaled back by s_x * s_w (the inverse of Eq. 1); Table 5 compares
@@ -17,11 +17,20 @@
 // 32-byte k-slice for both operands.
 //
 // Tile: BM x BN outputs per workgroup, BKB bytes of every row per pipeline stage, two LDS stages.
-// Global -> registers -> LDS for stage t+1 is issued before the MFMAs of stage t.
 // LDS rows are BKB bytes; the 16-byte chunk index is XOR-swizzled with the row so that the 16
 // lanes that read the same chunk column of 16 consecutive rows hit 16 different bank groups.
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on
 // a contiguous band of tiles, walked in groups of GROUP_M tile-rows for L2 reuse.
+//
+// Two pipelines:
+//   gemm_dma_kernel   global -> LDS directly (global_load_lds_dwordx4: a wave fills one contiguous
+//                     1 KiB block of the stage per instruction, each lane fetching the global chunk
+//                     that belongs at its LDS position), stage t+1 in flight while stage t is
+//                     multiplied; MFMA operands double-buffered in registers so that the LDS reads
+//                     of k-slice s+1 are issued before the MFMAs of k-slice s.  Large problems.
+//   gemm_reg_kernel   global -> registers -> LDS, smaller tiles.  Small problems.
+#include <type_traits>
+
 #include "fq_internal.h"
 
 namespace fq {
@@ -31,26 +40,457 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef unsigned short v4us __attribute__((ext_vector_type(4)));
 
 enum { MODE_I8 = 0, MODE_I4 = 1, MODE_BF16 = 2 };
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+#define FQ_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define FQ_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of the wave
+// writes LDS bytes [lds_base + 16 i, +16).  lds_base is wave-uniform and travels in M0.
+// Written as inline assembly so that the outstanding-copy count (vmcnt) is managed by the kernel
+// itself: several stages stay in flight across barriers, which the compiler's conservative
+// "wait for every LDS DMA before any LDS read" rule would forbid.
+__device__ __forceinline__ void dma16(const uint8_t* uniform_base, uint32_t lane_offset, uint32_t lds_base)
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                 :
+                 : "s"(uniform_base), "v"(lane_offset), "s"(lds_base)
+                 : "memory");
 }
+__device__ __forceinline__ void dma16_addr(const uint8_t* lane_address, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(lane_address), "s"(lds_base)
+                 : "memory");
+}
+
+// 16 zero bytes in device memory: the source of DMA lanes that fall beyond the end of a row.
+__device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
 
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
 
+// Workgroup id -> output tile.  Ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous
+// band of the logical tile sequence, which walks GROUP_M tile-rows at a time.
+__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int& tile_m, int& tile_n)
+{
+    constexpr int GROUP_M = 8;
+    const int nwg = gridDim.x;
+    const int wg = blockIdx.x;
+    const int q = nwg >> 3, rem = nwg & 7;
+    const int xcd = wg & 7, idx = wg >> 3;
+    const int logical = (xcd < rem) ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
+    const int group = GROUP_M * tiles_n;
+    const int gidx = logical / group;
+    const int first_m = gidx * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int in_group = logical - gidx * group;
+    tile_m = first_m + in_group % gsz;
+    tile_n = in_group / gsz;
+}
+
+// Epilogue of one wave.  The MFMAs are issued with the W fragment as the first operand and the X
+// fragment as the second, so in the 32x32 accumulator block (i, j) lane l holds output row
+// 32 i + l%32 and, in registers 4g..4g+3, the four consecutive output columns
+// 32 j + 8 g + 4 (l/32) + 0..3: they are scaled, converted and written as one 8- or 16-byte store.
+template <int YDT> struct OutVec;
+template <> struct OutVec<FQ_I32> { typedef int type __attribute__((ext_vector_type(4))); };
+template <> struct OutVec<FQ_F32> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct OutVec<FQ_F16> { typedef _Float16 type __attribute__((ext_vector_type(4))); };
+template <> struct OutVec<FQ_BF16> { typedef __bf16 type __attribute__((ext_vector_type(4))); };
+
+template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typename Acc<MODE>::type const& acc, int r, float scale)
+{
+    if constexpr (MODE == MODE_BF16) {
+        return (__bf16)acc[r];
+    } else {
+        int v = acc[r];
+        if (MODE == MODE_I4) v >>= 8;
+        if constexpr (YDT == FQ_I32) return v;
+        else if constexpr (YDT == FQ_F32) return (float)v * scale;
+        else if constexpr (YDT == FQ_BF16) return (__bf16)((float)v * scale);
+        else return (_Float16)((float)v * scale);
+    }
+}
+
+template <int MODE, int YDT, int FM, int FN, typename acc_t>
+__device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N, float scale,
+                                              void* __restrict__ Y, int ldy, bool fast)
+{
+    typedef typename OutVec<YDT>::type vec_t;
+    typedef decltype(convert_out<MODE, YDT>(acc[0][0], 0, scale)) elem_t;
+    const int lane = threadIdx.x & 63;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    elem_t* Yt = static_cast<elem_t*>(Y);
+    if (fast) {
+        // whole wave tile inside the matrix, rows aligned for vector stores
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            elem_t* yrow = Yt + (size_t)(row0 + i * 32 + frow) * ldy + col0 + 4 * fhalf;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    vec_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale);
+                    *reinterpret_cast<vec_t*>(yrow + j * 32 + 8 * g) = v;
+                }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int row = row0 + i * 32 + frow;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int col = col0 + j * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    if (row < M && col < N) Yt[(size_t)row * ldy + col] = convert_out<MODE, YDT>(acc[i][j], r, scale);
+                }
+        }
+    }
+}
+
+// 2-byte outputs of an interior tile go through a wave-private LDS staging area so that global
+// memory sees full 128-byte row segments: the wave writes its tile as [row][column] (16-byte units
+// XOR-swizzled with the row to spread banks), reads it back 16 bytes per lane, and stores 16 bytes
+// per lane with 64/UNITS complete rows per instruction.  `stage` must hold FM*32 x FN*32 x 2 bytes.
+template <int MODE, int YDT, int FM, int FN, typename acc_t>
+__device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row0, int col0, float scale,
+                                                   void* __restrict__ Y, int ldy, uint8_t* stage)
+{
+    typedef typename OutVec<YDT>::type vec_t;              // 4 x 2 bytes
+    constexpr int ROWB = FN * 32 * 2;                      // bytes per staged row
+    constexpr int UNITS = ROWB / 16;
+    constexpr int SW = (UNITS >= 8 ? 8 : UNITS) - 1;
+    constexpr int ROWS_PER_INSTR = 64 / UNITS;
+    static_assert(sizeof(vec_t) == 8 && (FM * 32) % ROWS_PER_INSTR == 0, "staging layout");
+    const int lane = threadIdx.x & 63;
+    const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = i * 32 + frow;
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                vec_t v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale);
+                const int u = g + 4 * j;
+                *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ (m & SW)) << 4) + 8 * fhalf) = v;
+            }
+    }
+    uint8_t* Yb = static_cast<uint8_t*>(Y);
+    const int mr = lane / UNITS, us = lane % UNITS;
+#pragma unroll
+    for (int t = 0; t < FM * 32 / ROWS_PER_INSTR; ++t) {
+        const int m = t * ROWS_PER_INSTR + mr;
+        const int u = us ^ (m & SW);
+        const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
+        *reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + m) * ldy + col0) * 2 + (u << 4)) = d;
+    }
+}
+
+template <int MODE, int FM, int FN, typename acc_t>
+__device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N,
+                                           const float* __restrict__ s_x, const float* __restrict__ s_w,
+                                           void* __restrict__ Y, int y_dtype, int ldy, uint8_t* stage = nullptr)
+{
+    const bool fast = row0 + FM * 32 <= M && col0 + FN * 32 <= N && (ldy & 3) == 0 &&
+                      (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+    const bool staged = fast && stage != nullptr && (ldy & 7) == 0 && (col0 & 7) == 0;
+    if constexpr (MODE == MODE_BF16) {
+        if (staged) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, 1.0f, Y, ldy, stage);
+        else store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, 1.0f, Y, ldy, fast);
+    } else {
+        if (y_dtype == FQ_I32) {
+            store_tile_as<MODE, FQ_I32, FM, FN>(acc, row0, col0, M, N, 1.0f, Y, ldy, fast);
+            return;
+        }
+        const float scale = (*s_x) * (*s_w);
+        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
+        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
+        else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+        else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+        else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+    }
+}
+
+// The MFMAs of one 32-byte k-slice for a wave: FM x FN blocks.
+template <int MODE, int FM, int FN, typename acc_t>
+__device__ __forceinline__ void mfma_slice(const v4i (&a)[FM], const v4i (&b)[FN], acc_t (&acc)[FM][FN])
+{
+    if constexpr (MODE == MODE_I8) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j], a[i], acc[i][j], 0, 0, 0);
+    } else if constexpr (MODE == MODE_I4) {
+        v4i alo[FM], ahi[FM], blo[FN], bhi[FN];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            alo[i] = (a[i] << 4) & (int)0xf0f0f0f0;
+            ahi[i] = a[i] & (int)0xf0f0f0f0;
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            blo[j] = (b[j] << 4) & (int)0xf0f0f0f0;
+            bhi[j] = b[j] & (int)0xf0f0f0f0;
+        }
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[j], alo[i], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[j], ahi[i], acc[i][j], 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, b[j]),
+                                                                   __builtin_bit_cast(v8bf, a[i]), acc[i][j], 0, 0, 0);
+    }
+}
+
+// =============================================================================================
+// gemm_dma_kernel: direct global -> LDS stages, register double-buffered MFMA operands
+// =============================================================================================
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __restrict__ A,
+                                                                const uint8_t* __restrict__ B, int M, int N,
+                                                                int rowbytes, const float* __restrict__ s_x,
+                                                                const float* __restrict__ s_w,
+                                                                void* __restrict__ Y, int y_dtype, int ldy,
+                                                                int tiles_m, int tiles_n)
+{
+    constexpr int NW = WM * WN;
+    constexpr int CPR = BKB / 16;              // chunks per row per stage
+    constexpr int RPB = 64 / CPR;              // rows of one 1 KiB DMA block (one wave instruction)
+    constexpr int A_BLOCKS = BM / RPB / NW;    // DMA blocks per wave per stage
+    constexpr int B_BLOCKS = BN / RPB / NW;
+    constexpr int LPS = A_BLOCKS + B_BLOCKS;   // DMA instructions per wave per stage
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 32, FN = TN / 32;
+    constexpr int KS = BKB / 32;               // 32-byte k-slices per stage
+    constexpr int STAGE = (BM + BN) * BKB;
+    constexpr int SWZ_SHIFT = (CPR == 8) ? 1 : 2;
+    constexpr int SWZ_MASK = CPR - 1;
+    // s_waitcnt immediate that leaves at most (NSTAGE-2) stages of this wave's DMA outstanding
+    constexpr int VM_KEEP = (NSTAGE - 2) * LPS;
+    constexpr int WAIT_KEEP = (VM_KEEP & 0xf) | ((VM_KEEP >> 4) << 14) | 0x0f70;
+    constexpr int WAIT_ALL = 0x0f70;           // vmcnt(0)
+    static_assert(NSTAGE >= 2 && VM_KEEP < 64, "stage count");
+    static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "DMA blocks do not tile the stage");
+    static_assert((RPB * NW) % 16 == 0, "swizzle must repeat across a wave's DMA blocks");
+    static_assert(CPR == 4 || CPR == 8, "BKB must be 64 or 128");
+    typedef typename Acc<MODE>::type acc_t;
+
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    int tile_m, tile_n;
+    tile_of_workgroup(tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- DMA mapping.  Block b of a tile covers rows b*RPB .. b*RPB+RPB-1; lane i lands at
+    //      (row b*RPB + i/CPR, stored chunk i%CPR), which must hold global chunk (i%CPR) ^ swz(row).
+    //      Wave w owns blocks w, w+NW, ...  Rows beyond the matrix re-read its last row. ----
+    const int drow = lane / CPR;                                   // row within the block
+    const int dsw = ((wave * RPB + drow) >> SWZ_SHIFT) & SWZ_MASK;    // same for all of the wave's blocks
+    const int dchunk = (lane % CPR) ^ dsw;                          // global chunk this lane fetches
+    const int nk_full = rowbytes / BKB;
+    const int nk = nk_full + ((rowbytes % BKB) ? 1 : 0);
+    uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
+#pragma unroll
+    for (int j = 0; j < A_BLOCKS; ++j)
+        offA[j] = (uint32_t)min(m0 + (wave + j * NW) * RPB + drow, M - 1) * (uint32_t)rowbytes + dchunk * 16;
+#pragma unroll
+    for (int j = 0; j < B_BLOCKS; ++j)
+        offB[j] = (uint32_t)min(n0 + (wave + j * NW) * RPB + drow, N - 1) * (uint32_t)rowbytes + dchunk * 16;
+
+    const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
+    auto issue_stage = [&](int buf, int kb, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const uint32_t sA = lds0 + buf * STAGE;
+        const uint32_t sB = sA + BM * BKB;
+        const uint8_t* gA = A + kb;
+        const uint8_t* gB = B + kb;
+        if constexpr (!TAIL) {
+#pragma unroll
+            for (int j = 0; j < A_BLOCKS; ++j) dma16(gA, offA[j], sA + j * NW * 1024);
+#pragma unroll
+            for (int j = 0; j < B_BLOCKS; ++j) dma16(gB, offB[j], sB + j * NW * 1024);
+        } else {
+            // last, partial stage: lanes whose chunk lies at or beyond the row end fetch 16 zero bytes
+            // instead, so that every stage issues the same number of DMA instructions per wave
+            const bool ok = kb + dchunk * 16 < rowbytes;
+            const uint8_t* z = reinterpret_cast<const uint8_t*>(g_zero_chunk);
+#pragma unroll
+            for (int j = 0; j < A_BLOCKS; ++j) dma16_addr(ok ? gA + offA[j] : z, sA + j * NW * 1024);
+#pragma unroll
+            for (int j = 0; j < B_BLOCKS; ++j) dma16_addr(ok ? gB + offB[j] : z, sB + j * NW * 1024);
+        }
+    };
+    auto issue_any = [&](int stage_index) {
+        if (stage_index < nk_full) issue_stage(stage_index % NSTAGE, stage_index * BKB, std::false_type{});
+        else issue_stage(stage_index % NSTAGE, stage_index * BKB, std::true_type{});
+    };
+
+    // ---- fragment read offsets ----
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = (frow >> SWZ_SHIFT) & SWZ_MASK;
+    int kofs[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kofs[ks] = ((2 * ks + fhalf) ^ fsw) << 4;
+    const int a_rd = (wm * TM + frow) * BKB;
+    const int b_rd = BM * BKB + (wn * TN + frow) * BKB;
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // MFMA operands, double-buffered in registers.  slice(cur, rs, rks, rd): the MFMAs of the k-slice
+    // held in buffer `cur`; when `rd`, the operands of k-slice `rks` of the LDS stage at `rs` are read
+    // into the other buffer, two after each of the first MFMAs, in the order they will be needed
+    // (a0, b0, b1.., a1..).  Scheduling barriers pin that interleaving.
+    v4i a[2][FM], b[2][FN];
+    constexpr int NR = FM + FN;
+    auto read_frag = [&](const uint8_t* rs, int buf, int ks, int r) {
+        if (r == 0) a[buf][0] = *reinterpret_cast<const v4i*>(rs + a_rd + kofs[ks]);
+        else if (r <= FN) b[buf][r - 1] = *reinterpret_cast<const v4i*>(rs + b_rd + (r - 1) * 32 * BKB + kofs[ks]);
+        else a[buf][r - FN] = *reinterpret_cast<const v4i*>(rs + a_rd + (r - FN) * 32 * BKB + kofs[ks]);
+    };
+    auto slice = [&](int cur, const uint8_t* rs, int rks, bool rd) {
+        const int nxt = cur ^ 1;
+        if constexpr (MODE == MODE_I4) {
+            v4i alo[FM], ahi[FM], blo[FN], bhi[FN];
+#pragma unroll
+            for (int t = 0; t < 2 * FM * FN; ++t) {
+                const int sub = t / (FM * FN), idx = t % (FM * FN), i = idx / FN, j = idx % FN;
+                // widen an operand the first time it is needed
+                if (sub == 0) {
+                    if (j == 0) alo[i] = (a[cur][i] << 4) & (int)0xf0f0f0f0;
+                    if (i == 0) blo[j] = (b[cur][j] << 4) & (int)0xf0f0f0f0;
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[j], alo[i], acc[i][j], 0, 0, 0);
+                } else {
+                    if (j == 0) ahi[i] = a[cur][i] & (int)0xf0f0f0f0;
+                    if (i == 0) bhi[j] = b[cur][j] & (int)0xf0f0f0f0;
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[j], ahi[i], acc[i][j], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (rd && 2 * t < NR) {
+                    read_frag(rs, nxt, rks, 2 * t);
+                    if (2 * t + 1 < NR) read_frag(rs, nxt, rks, 2 * t + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < FM * FN; ++t) {
+                const int i = t / FN, j = t % FN;
+                if constexpr (MODE == MODE_I8)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[cur][j], a[cur][i], acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, b[cur][j]),
+                                                                       __builtin_bit_cast(v8bf, a[cur][i]), acc[i][j],
+                                                                       0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rd && 2 * t < NR) {
+                    read_frag(rs, nxt, rks, 2 * t);
+                    if (2 * t + 1 < NR) read_frag(rs, nxt, rks, 2 * t + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    };
+
+    if constexpr (PIPE == 0) {
+        // ---- end-of-stage barrier, NSTAGE buffers: NSTAGE-1 stages in flight ----
+#pragma unroll
+        for (int st = 0; st < NSTAGE - 1; ++st)
+            if (st < nk) issue_any(st);
+        if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+        else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        __syncthreads();
+
+        int buf = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const uint8_t* s = smem + buf * STAGE;
+            buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
+            // the buffer refilled here was multiplied in iteration kt-1; every wave has passed that barrier
+            const bool steady = kt + NSTAGE - 1 < nk;
+            if (steady) issue_any(kt + NSTAGE - 1);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) read_frag(s, 0, 0, r);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) slice(ks & 1, s, ks + 1, ks + 1 < KS);
+            // this wave's DMA for stage kt+1 has landed (later stages may still be in flight)
+            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+            __syncthreads();
+        }
+    } else {
+        // ---- two buffers, barrier before the LAST k-slice of a stage.  By then every wave holds the
+        //      operands of that slice in registers, so the stage's buffer is free: the barrier both
+        //      publishes stage kt+1 (each wave waited for its own DMA) and releases buffer kt for the
+        //      DMA of stage kt+2, and the MFMAs of the last slice overlap the first LDS reads of
+        //      stage kt+1, so no wave idles behind the barrier waiting for operands. ----
+        static_assert(PIPE == 0 || (NSTAGE == 2 && KS % 2 == 0), "mid-stage barrier pipeline needs 2 buffers, even KS");
+        issue_any(0);
+        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+        __syncthreads();
+        if (nk > 1) issue_any(1);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) read_frag(smem, 0, 0, r);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const uint8_t* s = smem + (kt & 1) * STAGE;
+            const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE;
+#pragma unroll
+            for (int ks = 0; ks < KS - 1; ++ks) slice(ks & 1, s, ks + 1, true);
+            __builtin_amdgcn_s_waitcnt(0x0070);  // last slice's operands are in registers; my DMA of stage kt+1 landed
+            __syncthreads();
+            if (kt + 2 < nk) issue_any(kt + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            slice((KS - 1) & 1, sn, 0, kt + 1 < nk);
+        }
+    }
+
+    // After the last barrier of the loop no wave reads the stage buffers any more (the operands of
+    // the final k-slice are in registers), so each wave may reuse its share of LDS to stage its output.
+    constexpr bool CAN_STAGE = NW * TM * TN * 2 <= NSTAGE * STAGE;
+    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                             CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr);
+}
+
+// =============================================================================================
+// gemm_reg_kernel: global -> registers -> LDS
+// =============================================================================================
 template <int MODE, int BM, int BN, int BKB, int WM, int WN>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const uint8_t* __restrict__ A,
-                                                            const uint8_t* __restrict__ B, int M, int N,
-                                                            int rowbytes, const float* __restrict__ s_x,
-                                                            const float* __restrict__ s_w, void* __restrict__ Y,
-                                                            int y_dtype, int ldy, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __restrict__ A,
+                                                                const uint8_t* __restrict__ B, int M, int N,
+                                                                int rowbytes, const float* __restrict__ s_x,
+                                                                const float* __restrict__ s_w,
+                                                                void* __restrict__ Y, int y_dtype, int ldy,
+                                                                int tiles_m, int tiles_n)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BKB / 16;          // chunks per row per stage
@@ -63,7 +503,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const uint8_t* __rest
     constexpr int STAGE = (BM + BN) * BKB;
     constexpr int SWZ_SHIFT = (CPR == 8) ? 1 : 2;
     constexpr int SWZ_MASK = CPR - 1;
-    constexpr int GROUP_M = 8;
     static_assert(BM % RPP == 0 && BN % RPP == 0, "loader does not tile the block");
     static_assert(RPP % 16 == 0, "swizzle must repeat across loader passes");
     static_assert(CPR == 4 || CPR == 8, "BKB must be 64 or 128");
@@ -71,22 +510,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const uint8_t* __rest
 
     extern __shared__ __align__(16) uint8_t smem[];
 
-    // ---- workgroup -> tile ----
     int tile_m, tile_n;
-    {
-        const int nwg = gridDim.x;
-        const int wg = blockIdx.x;
-        const int q = nwg >> 3, rem = nwg & 7;
-        const int xcd = wg & 7, idx = wg >> 3;
-        const int logical = (xcd < rem) ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
-        const int group = GROUP_M * tiles_n;
-        const int gidx = logical / group;
-        const int first_m = gidx * GROUP_M;
-        const int gsz = min(tiles_m - first_m, GROUP_M);
-        const int in_group = logical - gidx * group;
-        tile_m = first_m + in_group % gsz;
-        tile_n = in_group / gsz;
-    }
+    tile_of_workgroup(tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -154,90 +579,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const uint8_t* __rest
             for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const v4i*>(s + a_rd + i * 32 * BKB + kofs[ks]);
 #pragma unroll
             for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const v4i*>(s + b_rd + j * 32 * BKB + kofs[ks]);
-            if constexpr (MODE == MODE_I8) {
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-            } else if constexpr (MODE == MODE_I4) {
-                v4i alo[FM], ahi[FM], blo[FN], bhi[FN];
-#pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    alo[i] = (a[i] << 4) & (int)0xf0f0f0f0;
-                    ahi[i] = a[i] & (int)0xf0f0f0f0;
-                }
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    blo[j] = (b[j] << 4) & (int)0xf0f0f0f0;
-                    bhi[j] = b[j] & (int)0xf0f0f0f0;
-                }
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], acc[i][j], 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(v8bf, a[i]), __builtin_bit_cast(v8bf, b[j]), acc[i][j], 0, 0, 0);
-            }
+            mfma_slice<MODE, FM, FN>(a, b, acc);
         }
         if (kt + 1 < nk) store_lds((kt + 1) & 1);
         __syncthreads();
     }
 
-    // ---- epilogue: accumulator layout of the 32x32 MFMA: lane -> column lane%32,
-    //      register r -> row 8*(r/4) + 4*(lane/32) + r%4 ----
-    float scale = 1.0f;
-    if (MODE != MODE_BF16 && y_dtype != FQ_I32) scale = (*s_x) * (*s_w);
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = n0 + wn * TN + j * 32 + frow;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                if (row < M && col < N) {
-                    const size_t o = (size_t)row * ldy + col;
-                    if constexpr (MODE == MODE_BF16) {
-                        static_cast<uint16_t*>(Y)[o] = f32_to_bf16_rne(acc[i][j][r]);
-                    } else {
-                        int v = acc[i][j][r];
-                        if (MODE == MODE_I4) v >>= 8;
-                        if (y_dtype == FQ_I32) {
-                            static_cast<int32_t*>(Y)[o] = v;
-                        } else {
-                            const float f = (float)v * scale;
-                            if (y_dtype == FQ_F32) static_cast<float*>(Y)[o] = f;
-                            else if (y_dtype == FQ_BF16) static_cast<uint16_t*>(Y)[o] = f32_to_bf16_rne(f);
-                            else static_cast<_Float16*>(Y)[o] = (_Float16)f;
-                        }
-                    }
-                }
-            }
-        }
+    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy);
 }
 
 // Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
 int g_variant = -1;
 
-template <int MODE, int BM, int BN, int BKB, int WM, int WN>
-int launch_variant(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x,
-                   const float* s_w, void* Y, int y_dtype, int ldy, hipStream_t stream)
+template <typename K>
+int launch_kernel(K kern, int BM, int BN, int BKB, int nstage, int threads, bool& attr_set, const void* A, const void* B,
+                  int M, int N, int rowbytes, const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
+                  hipStream_t stream)
 {
-    auto kern = gemm_kernel<MODE, BM, BN, BKB, WM, WN>;
-    constexpr int smem = 2 * (BM + BN) * BKB;
-    static bool attr_set = false;       // one per instantiation
+    const int smem = nstage * (BM + BN) * BKB;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -247,18 +606,37 @@ int launch_variant(const void* A, const void* B, int M, int N, int rowbytes, con
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const long long nwg = (long long)tiles_m * tiles_n;
     if (nwg > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
-    kern<<<dim3((unsigned)nwg), dim3(WM * WN * 64), smem, stream>>>(
-        static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype,
-        ldy, tiles_m, tiles_n);
+    kern<<<dim3((unsigned)nwg), dim3(threads), smem, stream>>>(static_cast<const uint8_t*>(A),
+                                                               static_cast<const uint8_t*>(B), M, N, rowbytes, s_x,
+                                                               s_w, Y, y_dtype, ldy, tiles_m, tiles_n);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
 }
 
-// variant 0: 256x256 tile, 128-byte stages, 8 waves (2x4)   — large problems
-// variant 1: 256x256 tile,  64-byte stages, 8 waves (2x4)
-// variant 2: 128x128 tile,  64-byte stages, 4 waves (2x2)   — small problems
-// variant 3: 256x128 tile, 128-byte stages, 8 waves (4x2)
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+               void* Y, int y_dtype, int ldy, hipStream_t stream)
+{
+    // the DMA kernel addresses rows with 32-bit byte offsets
+    if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
+        return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
+    static bool attr_set = false;
+    return launch_kernel(gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>, BM, BN, BKB, NSTAGE, WM * WN * 64, attr_set, A, B, M, N,
+                         rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+}
+
+template <int MODE, int BM, int BN, int BKB, int WM, int WN>
+int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+               void* Y, int y_dtype, int ldy, hipStream_t stream)
+{
+    static bool attr_set = false;
+    return launch_kernel(gemm_reg_kernel<MODE, BM, BN, BKB, WM, WN>, BM, BN, BKB, 2, WM * WN * 64, attr_set, A, B, M, N,
+                         rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+}
+
+constexpr int NUM_VARIANTS = 7;
+
 template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
              void* Y, int y_dtype, int ldy, hipStream_t stream)
@@ -269,10 +647,13 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         v = (big_tiles >= 192) ? 0 : 2;
     }
     switch (v) {
-    case 0: return launch_variant<MODE, 256, 256, 128, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 1: return launch_variant<MODE, 256, 256, 64, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 2: return launch_variant<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 3: return launch_variant<MODE, 256, 128, 128, 4, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 1: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 0>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 2: return launch_reg<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 3: return launch_dma<MODE, 256, 256, 64, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }
@@ -281,7 +662,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
 
 int set_gemm_variant(int v)
 {
-    if (v < -1 || v > 3) return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
+    if (v < -1 || v >= NUM_VARIANTS) return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     g_variant = v;
     return FQ_OK;
 }
