@@ -30,7 +30,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def event_time_ms(torch, fn, iters, warmup=2):
+def event_time_ms(torch, fn, iters, warmup=10):
     """Average duration of fn() over `iters` launches, HIP events on the current stream."""
     for _ in range(warmup):
         fn()
@@ -47,14 +47,16 @@ def event_time_ms(torch, fn, iters, warmup=2):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--configs", default="cfg3,cfg3i8", help="comma-separated workload names from fq_workloads")
     ap.add_argument("--variant", type=int, default=-1, help="force a GEMM tile variant (fq_gemm_select)")
     ap.add_argument("--static", action="store_true", help="static activation scale a' = T (the paper's mode)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time every GEMM variant per layer (stderr table)")
-    ap.add_argument("--kernels-only", action="store_true", help="skip the per-kernel breakdown of bf16 / flatten")
+    ap.add_argument("--align", type=int, default=0,
+                    help="padding of the flattened width (0: 128 channels for INT8, 256 for INT4, so that rows start "
+                         "on 128-byte boundaries; 32 is the paper's value)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1")
@@ -80,7 +82,7 @@ def main():
             sp = L.spec
             Xd = torch.from_numpy(L.X_store.view(np.int16)).to(dev).view(torch.bfloat16)
             Wd = torch.from_numpy(L.W_store.view(np.int16)).to(dev).view(torch.bfloat16)
-            lay = fq.FqLinear(Wd, L.chmax, L.T, sp.bits, device=dev)
+            lay = fq.FqLinear(Wd, L.chmax, L.T, sp.bits, device=dev, align=args.align)
             Y = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             Ybf = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             a_static = torch.tensor([L.T], dtype=torch.float32, device=dev) if args.static else None
@@ -217,7 +219,8 @@ def main():
                                ": LLaMA-7B FFN pair 4096->11008->4096 INT4 and 4096->4096 INT8 projection, M=8192 tokens, "
                                "bf16 activations with 0.5% outlier channels x[10,100], <=15% of channels flattened",
                    "activation_scale": "static a'=T" if args.static else "dynamic per-tensor absmax",
-                   "layers": [r["layer"] for r in rows], "gemm_variant": args.variant},
+                   "layers": [r["layer"] for r in rows], "gemm_variant": args.variant,
+                   "kpad_align": args.align if args.align else "128 (INT8) / 256 (INT4)"},
         "pct_int8_mfma_peak": round(100.0 * value / INT8_PEAK_TOPS, 2),
         "effective_tops": round(ops_eff / (t_step_ms * 1e-3) / 1e12, 2),
         "speedup_vs_bf16": round(t_bf16_total / t_step_ms, 3),

@@ -9,8 +9,8 @@
 //                  instruction; per-thread running max; one atomic max per column per block;
 //                  the max of non-negative floats is taken on their bit patterns, so the result
 //                  does not depend on the order of the updates)
-//   scale          one workgroup: per-tensor absmax a' by wavefront reductions, the scale s, and
-//                  the per-slot multiplier m_p = fl32(qmax / (n_p * a')) (float64 quotient)
+//   scale          per-tensor absmax a' by wavefront reductions, the scale s, and the per-slot
+//                  multiplier m_p = fl32(qmax / (n_p * a')) (float64 quotient)
 //   flatten_quant  each thread owns 16 consecutive flattened slots for a strip of rows: the map
 //                  and multipliers are read once into registers, then per row 16 values are
 //                  read (one contiguous 32/64-byte vector read when the slots are an identity
@@ -79,37 +79,63 @@ __global__ void fill_u32_kernel(uint32_t* p, int count, uint32_t v)
 // ---------------------------------------------------------------------------------------------
 // per input channel absmax
 // ---------------------------------------------------------------------------------------------
+// Workgroup = 4 waves.  The 64 lanes of a wave cover 64 adjacent 16-byte column groups (1 KiB of a
+// row per load); the 4 waves take interleaved rows of the block's row strip.  The 4 partial maxima
+// of a column meet in LDS and one lane issues the atomic max, and only if its value exceeds what the
+// column already holds (the stored value only grows, so a stale read can only cause a redundant
+// atomic, never a missed one).
 template <int DT>
 __global__ __launch_bounds__(256) void colabsmax_kernel(const void* __restrict__ Xv, int M, int K, int ld,
                                                         int rows_per_block, uint32_t* __restrict__ cmax)
 {
     typedef typename Elem<DT>::type T;
     constexpr int VEC = Elem<DT>::VEC;
+    __shared__ float part[4][64 * VEC];
     const T* X = static_cast<const T*>(Xv);
-    const int col0 = (blockIdx.x * 256 + threadIdx.x) * VEC;
-    if (col0 >= K) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col0 = (blockIdx.x * 64 + lane) * VEC;
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(M, r0 + rows_per_block);
     float mx[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) mx[v] = 0.0f;
     if (col0 + VEC <= K) {
-        const T* p = X + (size_t)r0 * ld + col0;
-#pragma unroll 4
-        for (int r = r0; r < r1; ++r, p += ld) {
-            v4u raw = *reinterpret_cast<const v4u*>(p);
+        const T* p = X + (size_t)(r0 + wave) * ld + col0;
+        const size_t step = (size_t)4 * ld;
+        int r = r0 + wave;
+        for (; r + 12 < r1; r += 16, p += 4 * step) {          // four rows in flight per lane
+            v4u raw[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) raw[q] = *reinterpret_cast<const v4u*>(p + q * step);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float f[VEC];
+                widen16<DT>(raw[q], f);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mx[v] = fmaxf(mx[v], fabsf(f[v]));
+            }
+        }
+        for (; r < r1; r += 4, p += step) {
             float f[VEC];
-            widen16<DT>(raw, f);
+            widen16<DT>(*reinterpret_cast<const v4u*>(p), f);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) mx[v] = fmaxf(mx[v], fabsf(f[v]));
         }
+    } else if (col0 < K) {                                       // ragged last column group
+        for (int v = 0; col0 + v < K; ++v)
+            for (int r = r0 + wave; r < r1; r += 4)
+                mx[v] = fmaxf(mx[v], fabsf(Elem<DT>::widen(X[(size_t)r * ld + col0 + v])));
+    }
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) atomicMax(&cmax[col0 + v], __float_as_uint(mx[v]));
-    } else {
-        for (int v = 0; col0 + v < K; ++v) {
-            float m = 0.0f;
-            for (int r = r0; r < r1; ++r) m = fmaxf(m, fabsf(Elem<DT>::widen(X[(size_t)r * ld + col0 + v])));
-            atomicMax(&cmax[col0 + v], __float_as_uint(m));
+    for (int v = 0; v < VEC; ++v) part[wave][lane * VEC + v] = mx[v];
+    __syncthreads();
+    // 256 threads finish 64*VEC columns
+    for (int c = threadIdx.x; c < 64 * VEC; c += 256) {
+        const int col = blockIdx.x * 64 * VEC + c;
+        if (col < K) {
+            const float m = fmaxf(fmaxf(part[0][c], part[1][c]), fmaxf(part[2][c], part[3][c]));
+            const uint32_t bits = __float_as_uint(m);
+            if (bits > __hip_atomic_load(&cmax[col], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(&cmax[col], bits);
         }
     }
 }
@@ -117,13 +143,34 @@ __global__ __launch_bounds__(256) void colabsmax_kernel(const void* __restrict__
 // ---------------------------------------------------------------------------------------------
 // per-tensor absmax, scale and per-slot multipliers (one workgroup)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_max(float v)
+// The per-tensor absmax of the flattened tensor is max_p fl32(c_p / n_p) with c_p the channel
+// maximum behind slot p and n_p its copy count.  Rounding is monotonic, so it equals
+// fl32(c* / n*) for the pair with the largest exact quotient; pairs are compared exactly by cross
+// multiplication in float64 (24-bit x n products, exact for n < 2^29), leaving a single division at
+// the end.
+struct Quot {
+    float c;
+    int n;
+};
+__device__ __forceinline__ Quot quot_max(Quot a, Quot b)
+{
+    return ((double)b.c * (double)a.n > (double)a.c * (double)b.n) ? b : a;
+}
+__device__ __forceinline__ Quot wave_quot_max(Quot q)
 {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    for (int off = 32; off >= 1; off >>= 1) {
+        Quot o;
+        o.c = __shfl_xor(q.c, off, 64);
+        o.n = __shfl_xor(q.n, off, 64);
+        q = quot_max(q, o);
+    }
+    return q;
 }
 
+// Every workgroup recomputes the absmax a' (a cheap reduction over the map), tabulates the
+// multipliers m(n) = fl32(qmax / (n * a')) for n < 1024 in LDS (one float64 division per thread),
+// and fills its own 1024 slots of mslot.  Workgroup 0 also writes the scale.
 __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict__ cmax, int K,
                                                      const int32_t* __restrict__ src,
                                                      const int32_t* __restrict__ rep, int Kpad, int qmax,
@@ -131,29 +178,29 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
                                                      float* __restrict__ mslot, float* __restrict__ scale_out,
                                                      float* __restrict__ scalars)
 {
-    __shared__ float red[16];
+    __shared__ Quot red[16];
     __shared__ float a_shared;
+    __shared__ float table[1024];
     const int tid = threadIdx.x;
-    float a = 0.0f;
-    if (mode == 0) {
-        // a' = max over slots of fl32(cmax[src] / n); the float64 quotient rounded to fp32 is the
-        // correctly rounded fp32 quotient (53 >= 2*24 + 2 bits)
-        for (int p = tid; p < Kpad; p += 1024) {
-            int s = src[p], n = rep[p];
-            if ((unsigned)s < (unsigned)K && n > 0)
-                a = fmaxf(a, (float)((double)__uint_as_float(cmax[s]) / (double)n));
-        }
-    } else if (mode == 2) {
-        for (int j = tid; j < K; j += 1024) a = fmaxf(a, __uint_as_float(cmax[j]));
-    }
+    float a;
     if (mode != 1) {
-        a = wave_max(a);
-        if ((tid & 63) == 0) red[tid >> 6] = a;
+        Quot best = {0.0f, 1};
+        if (mode == 0) {
+            for (int p = tid; p < Kpad; p += 1024) {
+                const int s = src[p], n = rep[p];
+                if ((unsigned)s < (unsigned)K && n > 0) best = quot_max(best, Quot{__uint_as_float(cmax[s]), n});
+            }
+        } else {
+            for (int j = tid; j < K; j += 1024) best = quot_max(best, Quot{__uint_as_float(cmax[j]), 1});
+        }
+        best = wave_quot_max(best);
+        if ((tid & 63) == 0) red[tid >> 6] = best;
         __syncthreads();
         if (tid < 64) {
-            float t = (tid < 16) ? red[tid] : 0.0f;
-            t = wave_max(t);
-            if (tid == 0) a_shared = t;
+            Quot t = (tid < 16) ? red[tid] : Quot{0.0f, 1};
+            t = wave_quot_max(t);
+            // the float64 quotient rounded to fp32 is the correctly rounded fp32 quotient
+            if (tid == 0) a_shared = (float)((double)t.c / (double)t.n);
         }
         __syncthreads();
         a = a_shared;
@@ -162,15 +209,20 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
         if (!(a >= 0.0f) || a > 3.0e38f) a = 0.0f;     // negative / NaN / Inf static bound: treated as 0
     }
     const double ad = (double)a;
-    if (tid == 0) {
+    if (blockIdx.x == 0 && tid == 0) {
         *scale_out = (a == 0.0f) ? 1.0f : (float)(ad / (double)qmax);
         scalars[0] = a;
     }
-    for (int p = tid; p < Kpad; p += 1024) {
-        int s = src[p];
-        int n = (mode == 2) ? 1 : rep[p];
-        bool valid = (unsigned)s < (unsigned)K && n > 0 && a != 0.0f;
-        mslot[p] = valid ? (float)((double)qmax / ((double)n * ad)) : 0.0f;
+    table[tid] = (tid > 0 && a != 0.0f) ? (float)((double)qmax / ((double)tid * ad)) : 0.0f;
+    __syncthreads();
+    const int p = blockIdx.x * 1024 + tid;
+    if (p < Kpad) {
+        const int s = src[p];
+        const int n = (mode == 2) ? 1 : rep[p];
+        const bool valid = (unsigned)s < (unsigned)K && n > 0 && a != 0.0f;
+        float m = 0.0f;
+        if (valid) m = (n < 1024) ? table[n] : (float)((double)qmax / ((double)n * ad));
+        mslot[p] = m;
     }
 }
 
@@ -272,15 +324,16 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     const int qmax = (1 << (bits - 1)) - 1;
     if (mode != 1) {
         fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(ws.cmax, K, 0u);
-        const int bx = (K + 256 * VEC - 1) / (256 * VEC);
-        // aim at about 2048 workgroups; between 8 and 256 rows each
+        const int bx = (K + 64 * VEC - 1) / (64 * VEC);
+        // aim at about 2048 workgroups (8 per CU); between 16 and 512 rows each
         long long rpb = ((long long)M * bx + 2047) / 2048;
-        if (rpb < 8) rpb = 8;
-        if (rpb > 256) rpb = 256;
+        rpb = (rpb + 15) / 16 * 16;
+        if (rpb < 16) rpb = 16;
+        if (rpb > 512) rpb = 512;
         dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
         colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, ws.cmax);
     }
-    scale_kernel<<<1, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
+    scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
                                          scale_out, ws.scalars);
     const int G = Kpad / 16;
     // rows per thread: as many as 16 while the launch still has >= 2048 waves

@@ -8,11 +8,16 @@ from . import binding as B
 class FqLinear:
     """Offline: plan from (chmax, T) and quantize/repeat W.  Online: forward(X) -> Y."""
 
-    def __init__(self, W, chmax: np.ndarray, T: float, bits: int, device="cuda:0", align: int = 32):
+    def __init__(self, W, chmax: np.ndarray, T: float, bits: int, device="cuda:0", align: int = 0):
+        """align = 0 picks the flattened-width padding that makes every quantized row start on a
+        128-byte boundary (128 channels for INT8, 256 for packed INT4), which the GEMM's direct
+        global-to-LDS copies want; any multiple of 32 (the paper's padding) is accepted."""
         import torch
         self.torch = torch
         self.bits = bits
         self.N, self.K = W.shape
+        if align == 0:
+            align = 128 if bits == 8 else 256
         src, rep, self.Kprime, self.Kpad = B.fq_flatten_plan(chmax, T, align)
         self.src_host, self.rep_host = src, rep
         self.src = torch.from_numpy(src).to(device)

@@ -124,10 +124,12 @@ def test_flatten_quant_act_strided_rows_zero_input_and_bad_map():
 @pytest.mark.parametrize("cfg,over", [("cfg1b", {}), ("cfg2", dict(M_override=64, K_override=1024, N_override=301))])
 def test_flatten_weights(cfg, over, bits):
     L = _layer(cfg, **over)
-    src, rep, kp, kpad = fq.fq_flatten_plan(L.chmax, L.T)
     Wd = to_dev(L.W_store, L.spec.w_dtype)
     lay = fq.FqLinear(Wd, L.chmax, L.T, bits)
     torch.cuda.synchronize()
+    align = 128 if bits == 8 else 256                      # the layer's default row alignment
+    src, rep, kp, kpad = O.plan(L.chmax, L.T, align)
+    assert (lay.src_host == src).all() and (lay.rep_host == rep).all() and lay.Kpad == kpad
     Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
     want = Wq_o.view(np.uint8) if bits == 8 else O.pack_i4(Wq_o)
     assert np.float32(lay.s_w.item()) == s_w_o
@@ -215,10 +217,11 @@ def _run_linear(L, bits, ydt, a_static=None):
 ])
 def test_linear_end_to_end(cfg, over, bits):
     L = _layer(cfg, **over)
-    src, rep, kp, kpad = O.plan(L.chmax, L.T)
+    src, rep, kp, kpad = O.plan(L.chmax, L.T, 128 if bits == 8 else 256)
     Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
     acc_o, y_o, s_x_o = O.linear(L.X, src, rep, Wq_o, s_w_o, bits)
     lay, acc = _run_linear(L, bits, torch.int32)
+    assert (lay.src_host == src).all() and (lay.rep_host == rep).all()
     assert np.array_equal(acc.cpu().numpy(), acc_o)
     _, y32 = _run_linear(L, bits, torch.float32)
     assert rel_err(y32.cpu().numpy().astype(np.float64), y_o).max() <= 1e-6
