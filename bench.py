@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--align", type=int, default=0,
                     help="padding of the flattened width (0: 128 channels for INT8, 256 for INT4, so that rows start "
                          "on 128-byte boundaries; 32 is the paper's value)")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="also run one plain 1 GiB device copy (the reference kernel for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1")
@@ -171,6 +174,14 @@ def main():
                     avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])
     flatten_roofline = dict(bound="hbm", kernel="colabsmax + scale + flatten_quant", achieved=round(fqa["bytes"] / fqa["ms"] / 1e6, 1),
                             peak=HBM_PEAK_GBS, unit="GB/s", frac=round(fqa["bytes"] / fqa["ms"] / 1e6 / HBM_PEAK_GBS, 4))
+
+    if args.copy_ref:
+        src_buf = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst_buf = torch.empty_like(src_buf)
+        for _ in range(3):
+            dst_buf.copy_(src_buf)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src_buf, dst_buf
 
     # ---------------- CPU oracle on a bounded sample ----------------
     cpu = None

@@ -19,6 +19,9 @@
  *        the low nibble); Wq likewise [N, Kpad] / [N, Kpad/2].  Rows are densely packed.
  *   Y    [M, N] row-major, row stride ldy elements.
  *   Kpad must be a multiple of 32 (Sec. 5.1 pads the flattened channel count to a multiple of 32).
+ *   The GEMMs run fastest when every quantized row starts on a 128-byte boundary, i.e. when the plan
+ *   is made with align = 128 for INT8 and 256 for INT4 (the extra zero columns cost no MFMA work:
+ *   a k-stage is 128 bytes of a row in any case).
  *
  * Conventions common to every call
  *   - Returns FQ_OK (0) or an FQ_ERR_* code; fq_last_error_string() (thread-local) says why.
@@ -173,10 +176,14 @@ size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits);
 int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * fq_gemm_select — tuning hook for benchmarks: force the tile variant used by fq_gemm_i8 /
+ * fq_gemm_select — tuning hook for benchmarks: force the kernel variant used by fq_gemm_i8 /
  * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
- *   0: 256x256 tile, 128-byte k-stages, 8 waves    1: 256x256 tile, 64-byte k-stages, 8 waves
- *   2: 128x128 tile,  64-byte k-stages, 4 waves    3: 256x128 tile, 128-byte k-stages, 8 waves
+ *   0: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, barrier before the last
+ *      k-slice of a stage (the large-problem kernel)
+ *   1: as 0 with the barrier at the end of the stage
+ *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)
+ *   3: as 0 with 64-byte k-stages        4: as 0 with 4 waves (128x128 per wave)
+ *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies
  * Every variant computes the same values.  Returns FQ_ERR_RANGE for an unknown variant.
  * ------------------------------------------------------------------------------------------- */
 int fq_gemm_select(int variant);

@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
     const T* row = X + (size_t)r0 * ld;
 
-#pragma unroll 2
+#pragma unroll 4
     for (int r = r0; r < r1; ++r, row += ld, o += orow_bytes) {
         float x[16];
         if (contig) {
@@ -325,8 +325,8 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     if (mode != 1) {
         fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(ws.cmax, K, 0u);
         const int bx = (K + 64 * VEC - 1) / (64 * VEC);
-        // aim at about 2048 workgroups (8 per CU); between 16 and 512 rows each
-        long long rpb = ((long long)M * bx + 2047) / 2048;
+        // aim at about 1024 workgroups (4 per CU); between 16 and 512 rows each
+        long long rpb = ((long long)M * bx + 1023) / 1024;
         rpb = (rpb + 15) / 16 * 16;
         if (rpb < 16) rpb = 16;
         if (rpb > 512) rpb = 512;
