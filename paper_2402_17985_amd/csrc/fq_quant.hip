@@ -80,7 +80,8 @@ __global__ void fill_u32_kernel(uint32_t* p, int count, uint32_t v)
 // per input channel absmax
 // ---------------------------------------------------------------------------------------------
 // Workgroup = 4 waves.  The 64 lanes of a wave cover 64 adjacent 16-byte column groups (1 KiB of a
-// row per load); the 4 waves take interleaved rows of the block's row strip.  The 4 partial maxima
+// row per load); the 4 waves take interleaved rows of the block's row strip, each lane keeping
+// sixteen loads in flight.  The 4 partial maxima
 // of a column meet in LDS and one lane issues the atomic max, and only if its value exceeds what the
 // column already holds (the stored value only grows, so a stale read can only cause a redundant
 // atomic, never a missed one).
@@ -100,10 +101,23 @@ __global__ __launch_bounds__(256) void colabsmax_kernel(const void* __restrict__
 #pragma unroll
     for (int v = 0; v < VEC; ++v) mx[v] = 0.0f;
     if (col0 + VEC <= K) {
+        // wave w takes rows r0 + w, r0 + w + 4, ...; sixteen 16-byte loads in flight per lane
         const T* p = X + (size_t)(r0 + wave) * ld + col0;
         const size_t step = (size_t)4 * ld;
         int r = r0 + wave;
-        for (; r + 12 < r1; r += 16, p += 4 * step) {          // four rows in flight per lane
+        for (; r + 60 < r1; r += 64, p += 16 * step) {
+            v4u raw[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) raw[q] = *reinterpret_cast<const v4u*>(p + q * step);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                float f[VEC];
+                widen16<DT>(raw[q], f);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mx[v] = fmaxf(mx[v], fabsf(f[v]));
+            }
+        }
+        for (; r + 12 < r1; r += 16, p += 4 * step) {
             v4u raw[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) raw[q] = *reinterpret_cast<const v4u*>(p + q * step);
@@ -248,7 +262,13 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     constexpr int VEC = Elem<DT>::VEC;
     const T* X = static_cast<const T*>(Xv);
     const int G = Kpad >> 4;                                   // groups of 16 slots per row
-    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Remap them so that
+    // consecutive logical workgroups (the head and the gathered tail of the same rows) share an XCD:
+    // the tail's gathers then hit the lines the head has just brought into that L2.
+    const unsigned nwg = gridDim.x, wg = blockIdx.x;
+    const unsigned q = nwg >> 3, rem = nwg & 7, xcd = wg & 7, idx = wg >> 3;
+    const unsigned lwg = (xcd < rem) ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
+    const long long gid = (long long)lwg * 256 + threadIdx.x;
     const int g = (int)(gid % G);
     const long long rt = gid / G;
     const long long r0l = rt * rows_per_thread;
@@ -325,10 +345,11 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     if (mode != 1) {
         fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(ws.cmax, K, 0u);
         const int bx = (K + 64 * VEC - 1) / (64 * VEC);
-        // aim at about 1024 workgroups (4 per CU); between 16 and 512 rows each
+        // a workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves); aim at
+        // about 1024 workgroups, at most 512 rows each
         long long rpb = ((long long)M * bx + 1023) / 1024;
-        rpb = (rpb + 15) / 16 * 16;
-        if (rpb < 16) rpb = 16;
+        rpb = (rpb + 63) / 64 * 64;
+        if (rpb < 128) rpb = 128;
         if (rpb > 512) rpb = 512;
         dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
         colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, ws.cmax);
@@ -336,8 +357,8 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
                                          scale_out, ws.scalars);
     const int G = Kpad / 16;
-    // rows per thread: as many as 16 while the launch still has >= 2048 waves
-    int rpt = 16;
+    // rows per thread: as many as 8 while the launch still has >= 2048 waves
+    int rpt = 8;
     while (rpt > 1 && ((long long)G * ((M + rpt - 1) / rpt)) < 2048LL * 64) rpt >>= 1;
     const long long threads = (long long)G * ((M + rpt - 1) / rpt);
     const unsigned blocks = (unsigned)((threads + 255) / 256);

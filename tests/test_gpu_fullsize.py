@@ -1,0 +1,81 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(FqLinear defaults: automatic kernel choice, 128/256-channel row alignment, dynamic scale).
+
+What is compared: the flatten map, the quantized activations and weights and the scales in full
+(bit-exact); the int32 accumulators on sampled rows the oracle recomputes one by one (bit-exact)
+plus an exact int64 Freivalds identity over the whole matrix (acc r == Xq (Wq^T r) for a random
+vector r: any wrong accumulator changes the left side unless its r entry is 0, probability 2^-20
+per vector); the bf16 outputs on the sampled rows (relative 2^-8, see test_gpu_parity)."""
+import numpy as np
+import pytest
+import torch
+
+import fq_workloads as WL
+import paper_2402_17985_amd as fq
+from oracle import fq_oracle as O
+from tests.gpu_util import DEV, bf16_to_f64, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_layer(cfg_name, idx, n_sample_rows=40):
+    cfg = WL.CONFIGS[cfg_name]
+    L = WL.make_layer(cfg, idx)
+    sp = L.spec
+    bits = sp.bits
+    print(f"[fullsize] {cfg_name}.{sp.name} M={sp.M} K={sp.K} N={sp.N} bits={bits}", flush=True)
+    Wd = to_dev(L.W_store, sp.w_dtype)
+    lay = fq.FqLinear(Wd, L.chmax, L.T, bits)
+    Xd = to_dev(L.X_store, sp.x_dtype)
+    # --- map, weights ---
+    src, rep, kp, kpad = O.plan(L.chmax, L.T, 128 if bits == 8 else 256)
+    assert (lay.src_host == src).all() and (lay.rep_host == rep).all() and lay.Kpad == kpad
+    Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
+    Wq_g = lay.Wq.cpu().numpy().view(np.uint8)
+    assert np.float32(lay.s_w.item()) == s_w_o
+    assert np.array_equal(Wq_g, Wq_o.view(np.uint8) if bits == 8 else O.pack_i4(Wq_o))
+    # --- quantized activations (the workspace of fq_linear starts with X'q) ---
+    acc_g = lay.forward(Xd, out_dtype=torch.int32)
+    torch.cuda.synchronize()
+    cols = kpad if bits == 8 else kpad // 2
+    Xq_g = lay.workspace(sp.M)[: sp.M * cols].view(sp.M, cols).cpu().numpy()
+    a = O.act_absmax_dynamic(L.X, src, rep)
+    Xq_o, s_x_o = O.flatten_quant_act(L.X, src, rep, bits, a)
+    assert np.array_equal(Xq_g, Xq_o.view(np.uint8) if bits == 8 else O.pack_i4(Xq_o))
+    acc_g = acc_g.cpu().numpy()
+    # --- sampled rows, recomputed by the oracle ---
+    rng = np.random.default_rng(12345 + idx)
+    rows = np.unique(np.concatenate([[0, sp.M - 1, 255, 256], rng.integers(0, sp.M, n_sample_rows)]))
+    acc_o = O.gemm_i32(Xq_o[rows], Wq_o)
+    assert np.array_equal(acc_g[rows], acc_o)
+    # --- every accumulator at once: exact Freivalds identity in int64 ---
+    for rep_i in range(2):
+        r = rng.integers(0, 1 << 20, sp.N).astype(np.int64)
+        lhs = acc_g.astype(np.int64) @ r
+        t = r @ Wq_o.astype(np.int64)
+        rhs = Xq_o.astype(np.int64) @ t
+        assert np.array_equal(lhs, rhs)
+    # --- dequantized bf16 output on the samples ---
+    Y = lay.forward(Xd, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    y_o = O.dequant(acc_o, s_x_o, s_w_o)
+    assert rel_err(bf16_to_f64(Y[torch.from_numpy(rows).to(DEV)]), y_o).max() <= 2.0 ** -8
+
+
+def test_cfg2_full():
+    """LLaMA-7B q/k/v-style projection, INT8, M = 2048: every accumulator recomputed by the oracle."""
+    L = WL.make_layer(WL.CONFIGS["cfg2"], 0)
+    lay = fq.FqLinear(to_dev(L.W_store, "bf16"), L.chmax, L.T, 8)
+    acc = lay.forward(to_dev(L.X_store, "bf16"), out_dtype=torch.int32)
+    torch.cuda.synchronize()
+    Wq_o, s_w_o = O.flatten_weights(L.W, lay.src_host, 8)
+    acc_o, y_o, s_x_o = O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, 8)
+    assert np.array_equal(acc.cpu().numpy(), acc_o)
+    Y = lay.forward(to_dev(L.X_store, "bf16"), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert rel_err(bf16_to_f64(Y), y_o).max() <= 2.0 ** -8
+
+
+@pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg3i8", 0)])
+def test_benchmark_layers_full_size(cfg, idx):
+    _check_layer(cfg, idx)
