@@ -72,16 +72,21 @@ __device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
 
+__device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n);
+
 // Workgroup id -> output tile.  Ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous
 // band of the logical tile sequence, which walks GROUP_M tile-rows at a time.
-__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int& tile_m, int& tile_n)
+__device__ __forceinline__ void tile_of_workgroup(int wg, int nwg, int tiles_m, int tiles_n, int& tile_m,
+                                                  int& tile_n)
 {
-    constexpr int GROUP_M = 8;
-    const int nwg = gridDim.x;
-    const int wg = blockIdx.x;
     const int q = nwg >> 3, rem = nwg & 7;
     const int xcd = wg & 7, idx = wg >> 3;
     const int logical = (xcd < rem) ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
+    tile_of_logical(logical, tiles_m, tiles_n, tile_m, tile_n);
+}
+__device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n)
+{
+    constexpr int GROUP_M = 8;
     const int group = GROUP_M * tiles_n;
     const int gidx = logical / group;
     const int first_m = gidx * GROUP_M;
@@ -266,12 +271,10 @@ __device__ __forceinline__ void mfma_slice(const v4i (&a)[FM], const v4i (&b)[FN
 // gemm_dma_kernel: direct global -> LDS stages, register double-buffered MFMA operands
 // =============================================================================================
 template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __restrict__ A,
-                                                                const uint8_t* __restrict__ B, int M, int N,
-                                                                int rowbytes, const float* __restrict__ s_x,
-                                                                const float* __restrict__ s_w,
-                                                                void* __restrict__ Y, int y_dtype, int ldy,
-                                                                int tiles_m, int tiles_n)
+__device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
+                                              const uint8_t* __restrict__ B, int M, int N, int rowbytes,
+                                              const float* __restrict__ s_x, const float* __restrict__ s_w,
+                                              void* __restrict__ Y, int y_dtype, int ldy)
 {
     constexpr int NW = WM * WN;
     constexpr int CPR = BKB / 16;              // chunks per row per stage
@@ -294,12 +297,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
     static_assert((RPB * NW) % 16 == 0, "swizzle must repeat across a wave's DMA blocks");
     static_assert(CPR == 4 || CPR == 8, "BKB must be 64 or 128");
     typedef typename Acc<MODE>::type acc_t;
-
-    extern __shared__ __align__(16) uint8_t smem[];
-
-    int tile_m, tile_n;
-    tile_of_workgroup(tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -481,6 +478,36 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
                              CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr);
 }
 
+// The kernel.  Workgroups [0, n_main) compute full BM x BN tiles.  When the number of tiles leaves a
+// last, partly filled round of at most half the CUs, those tiles are instead computed as two
+// (BM/2) x BN halves by workgroups [n_main, n_main + 2 * n_tail), so that the last round takes about
+// half as long.
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __restrict__ A,
+                                                                const uint8_t* __restrict__ B, int M, int N,
+                                                                int rowbytes, const float* __restrict__ s_x,
+                                                                const float* __restrict__ s_w,
+                                                                void* __restrict__ Y, int y_dtype, int ldy,
+                                                                int tiles_m, int tiles_n, int n_main)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int wg = blockIdx.x;
+    int tile_m, tile_n;
+    if (wg < n_main) {
+        tile_of_workgroup(wg, n_main, tiles_m, tiles_n, tile_m, tile_n);
+        gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
+                                                                s_x, s_w, Y, y_dtype, ldy);
+    } else {
+        if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
+            const int t = wg - n_main;
+            tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
+            gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE>(smem, tile_m * BM + (t & 1) * (BM / 2),
+                                                                        tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
+                                                                        Y, y_dtype, ldy);
+        }
+    }
+}
+
 // =============================================================================================
 // gemm_reg_kernel: global -> registers -> LDS
 // =============================================================================================
@@ -511,7 +538,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
     extern __shared__ __align__(16) uint8_t smem[];
 
     int tile_m, tile_n;
-    tile_of_workgroup(tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -591,27 +618,28 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
 // Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
 int g_variant = -1;
 
-template <typename K>
-int launch_kernel(K kern, int BM, int BN, int BKB, int nstage, int threads, bool& attr_set, const void* A, const void* B,
-                  int M, int N, int rowbytes, const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
-                  hipStream_t stream)
+int set_lds_limit(const void* kern, int smem, bool& attr_set)
 {
-    const int smem = nstage * (BM + BN) * BKB;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipFuncSetAttribute(%d bytes LDS): %s", smem, hipGetErrorString(e));
         attr_set = true;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const long long nwg = (long long)tiles_m * tiles_n;
-    if (nwg > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
-    kern<<<dim3((unsigned)nwg), dim3(threads), smem, stream>>>(static_cast<const uint8_t*>(A),
-                                                               static_cast<const uint8_t*>(B), M, N, rowbytes, s_x,
-                                                               s_w, Y, y_dtype, ldy, tiles_m, tiles_n);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
+}
+
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
 }
 
 template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
@@ -621,18 +649,47 @@ int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const f
     // the DMA kernel addresses rows with 32-bit byte offsets
     if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
         return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
+    auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>;
+    constexpr int smem = NSTAGE * (BM + BN) * BKB;
     static bool attr_set = false;
-    return launch_kernel(gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>, BM, BN, BKB, NSTAGE, WM * WN * 64, attr_set, A, B, M, N,
-                         rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const long long tiles = (long long)tiles_m * tiles_n;
+    if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
+    // a last round that would occupy at most half of the CUs is run as half-height tiles instead
+    constexpr bool HALF_OK = BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0;
+    const int cus = compute_units();
+    const int r = (int)(tiles % cus);
+    int n_main = (int)tiles, n_tail = 0;
+    if (HALF_OK && r > 0 && 2 * r <= cus) {
+        n_tail = r;
+        n_main = (int)tiles - r;
+    }
+    kern<<<dim3((unsigned)(n_main + 2 * n_tail)), dim3(WM * WN * 64), smem, stream>>>(
+        static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+        tiles_m, tiles_n, n_main);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
 }
 
 template <int MODE, int BM, int BN, int BKB, int WM, int WN>
 int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                void* Y, int y_dtype, int ldy, hipStream_t stream)
 {
+    auto kern = gemm_reg_kernel<MODE, BM, BN, BKB, WM, WN>;
+    constexpr int smem = 2 * (BM + BN) * BKB;
     static bool attr_set = false;
-    return launch_kernel(gemm_reg_kernel<MODE, BM, BN, BKB, WM, WN>, BM, BN, BKB, 2, WM * WN * 64, attr_set, A, B, M, N,
-                         rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const long long tiles = (long long)tiles_m * tiles_n;
+    if (tiles > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
+    kern<<<dim3((unsigned)tiles), dim3(WM * WN * 64), smem, stream>>>(static_cast<const uint8_t*>(A),
+                                                                      static_cast<const uint8_t*>(B), M, N, rowbytes,
+                                                                      s_x, s_w, Y, y_dtype, ldy, tiles_m, tiles_n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
 }
 
 constexpr int NUM_VARIANTS = 7;
