@@ -18,8 +18,9 @@ from tests.gpu_util import DEV, bf16_to_f64, rel_err, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _check_layer(cfg_name, idx, n_sample_rows=40):
+def _check_layer(cfg_name, idx, n_sample_rows=40, freivalds=2):
     cfg = WL.CONFIGS[cfg_name]
+    print(f"[fullsize] generating {cfg_name} layer {idx}", flush=True)
     L = WL.make_layer(cfg, idx)
     sp = L.spec
     bits = sp.bits
@@ -34,6 +35,7 @@ def _check_layer(cfg_name, idx, n_sample_rows=40):
     Wq_g = lay.Wq.cpu().numpy().view(np.uint8)
     assert np.float32(lay.s_w.item()) == s_w_o
     assert np.array_equal(Wq_g, Wq_o.view(np.uint8) if bits == 8 else O.pack_i4(Wq_o))
+    print("[fullsize]   map, weights and s_w equal the oracle's", flush=True)
     # --- quantized activations (the workspace of fq_linear starts with X'q) ---
     acc_g = lay.forward(Xd, out_dtype=torch.int32)
     torch.cuda.synchronize()
@@ -43,18 +45,21 @@ def _check_layer(cfg_name, idx, n_sample_rows=40):
     Xq_o, s_x_o = O.flatten_quant_act(L.X, src, rep, bits, a)
     assert np.array_equal(Xq_g, Xq_o.view(np.uint8) if bits == 8 else O.pack_i4(Xq_o))
     acc_g = acc_g.cpu().numpy()
+    print("[fullsize]   quantized activations equal the oracle's", flush=True)
     # --- sampled rows, recomputed by the oracle ---
     rng = np.random.default_rng(12345 + idx)
     rows = np.unique(np.concatenate([[0, sp.M - 1, 255, 256], rng.integers(0, sp.M, n_sample_rows)]))
     acc_o = O.gemm_i32(Xq_o[rows], Wq_o)
     assert np.array_equal(acc_g[rows], acc_o)
+    print(f"[fullsize]   {len(rows)} sampled accumulator rows equal the oracle's", flush=True)
     # --- every accumulator at once: exact Freivalds identity in int64 ---
-    for rep_i in range(2):
+    for rep_i in range(freivalds):
         r = rng.integers(0, 1 << 20, sp.N).astype(np.int64)
         lhs = acc_g.astype(np.int64) @ r
         t = r @ Wq_o.astype(np.int64)
         rhs = Xq_o.astype(np.int64) @ t
         assert np.array_equal(lhs, rhs)
+        print("[fullsize]   Freivalds identity holds over the whole accumulator matrix", flush=True)
     # --- dequantized bf16 output on the samples ---
     Y = lay.forward(Xd, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
@@ -79,3 +84,15 @@ def test_cfg2_full():
 @pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg3i8", 0)])
 def test_benchmark_layers_full_size(cfg, idx):
     _check_layer(cfg, idx)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_cfg4_opt13b_layers_full_size(idx):
+    """OPT-13B-style layer, M = 8192: QKV and out projections INT8, FC1 / FC2 INT4."""
+    _check_layer("cfg4", idx, n_sample_rows=24, freivalds=1)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_cfg5_llama65b_layers_full_size(idx):
+    """LLaMA-65B-scale layer, M = 16384: attention projections INT8, FFN INT4."""
+    _check_layer("cfg5", idx, n_sample_rows=16, freivalds=1)
