@@ -21,6 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM-side bytes per launch of the dominant kernel (INT4 GEMM, average of its two launches per step) for
+# the default workload and kernel choice, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
+# by a plain 1 GiB copy in the same runs: profiles/pmc_traffic_bench_cfg3_m8192.txt.  Other workloads: null.
+MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.13e8}
+
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (INT4 is widened to int8 on chip: same ceiling)
 BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
@@ -185,7 +190,8 @@ def main():
     dom_avg_ms = dom["ms"] / dom["launches"]
     dom_achieved = dom["flops"] / dom["launches"] / dom_avg_ms / 1e9          # TOPS
     roofline = dict(bound="mfma", kernel=f"gemm_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
-                    peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4), traffic=None,
+                    peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get((args.configs, args.variant, args.align)),
                     avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])
     flatten_roofline = dict(bound="hbm", kernel="colabsmax + scale + flatten_quant", achieved=round(fqa["bytes"] / fqa["ms"] / 1e6, 1),
                             peak=HBM_PEAK_GBS, unit="GB/s", frac=round(fqa["bytes"] / fqa["ms"] / 1e6 / HBM_PEAK_GBS, 4))
@@ -199,34 +205,42 @@ def main():
         del src_buf, dst_buf
 
     # ---------------- CPU oracle on a bounded sample ----------------
+    # The same step (fq_linear per layer) on the host cores, layers taken largest first; a layer that
+    # would take longer than the budget is cut to its first rows.  About 20 s in total.
     cpu = None
     if not args.no_cpu:
         from oracle import fq_oracle as O
-        d = max(layers, key=lambda d: d["spec"].M * d["lay"].Kpad * d["spec"].N)
-        L, sp, lay = d["L"], d["spec"], d["lay"]
-        Wq_o, s_w_o = O.flatten_weights(L.W, lay.src_host, sp.bits)      # offline part, not timed
-        sample_rows = 16
-        t0 = time.perf_counter()
-        O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=sample_rows)
-        dt = time.perf_counter() - t0
-        # size the sample for roughly 15 s of oracle time
-        sample_rows = int(min(sp.M, max(16, sample_rows * 15.0 / max(dt, 1e-3))))
-        t0 = time.perf_counter()
-        acc_o, y_o, _ = O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=sample_rows)
-        dt = time.perf_counter() - t0
-        cpu_tops = 2.0 * sample_rows * lay.Kpad * sp.N / dt / 1e12
-        cpu = dict(value=round(cpu_tops, 5), unit="TOPS", cores=O.num_threads(), kind="oracle",
-                   sample=f"fq_linear (dynamic absmax over all {sp.M} rows, flatten-quantize + INT{sp.bits} GEMM + dequant) "
-                          f"on the first {sample_rows} of {sp.M} token rows of {d['name']} "
-                          f"(K={sp.K}, Kpad={lay.Kpad}, N={sp.N}); {dt:.1f} s")
-        # the sample doubles as a check of the timed configuration
-        got = torch.empty((sp.M, sp.N), dtype=torch.int32, device=dev)
-        lay.forward(d["X"], Y=got)
-        torch.cuda.synchronize()
-        same = bool(np.array_equal(got[:sample_rows].cpu().numpy(), acc_o))
-        log(f"[check] GPU accumulators equal the oracle's on the {sample_rows}-row sample: {same}")
-        if not same:
-            sys.exit("bench.py: GPU result differs from the oracle on the sampled rows")
+        budget, spent, ops, parts = 20.0, 0.0, 0.0, []
+        for d in sorted(layers, key=lambda d: -(d["spec"].M * d["lay"].Kpad * d["spec"].N)):
+            if spent >= 0.6 * budget:
+                break
+            L, sp, lay = d["L"], d["spec"], d["lay"]
+            Wq_o, s_w_o = O.flatten_weights(L.W, lay.src_host, sp.bits)      # offline part, not timed
+            t0 = time.perf_counter()
+            O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=64)
+            t_probe = time.perf_counter() - t0                                # includes the full-tensor absmax
+            t0 = time.perf_counter()
+            O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=128)
+            per_row = max((time.perf_counter() - t0 - t_probe) / 64.0, 1e-6)
+            nrows = int(min(sp.M, max(64, (budget - spent) / per_row)))
+            t0 = time.perf_counter()
+            acc_o, y_o, _ = O.linear(L.X, lay.src_host, lay.rep_host, Wq_o, s_w_o, sp.bits, row0=0, rows=nrows)
+            dt = time.perf_counter() - t0
+            spent += dt
+            ops += 2.0 * nrows * lay.Kpad * sp.N
+            parts.append(f"{d['name']}: first {nrows} of {sp.M} rows (Kpad={lay.Kpad}, N={sp.N}, INT{sp.bits}) {dt:.1f} s")
+            # the sample doubles as a check of the timed configuration
+            got = torch.empty((sp.M, sp.N), dtype=torch.int32, device=dev)
+            lay.forward(d["X"], Y=got)
+            torch.cuda.synchronize()
+            same = bool(np.array_equal(got[:nrows].cpu().numpy(), acc_o))
+            log(f"[check] {d['name']}: GPU accumulators equal the oracle's on the {nrows}-row sample: {same}")
+            if not same:
+                sys.exit("bench.py: GPU result differs from the oracle on the sampled rows")
+            del got, acc_o, y_o
+        cpu = dict(value=round(ops / spent / 1e12, 5), unit="TOPS", cores=O.num_threads(), kind="oracle",
+                   sample="fq_linear (dynamic absmax over all rows, flatten-quantize, integer GEMM, dequantize) on "
+                          + "; ".join(parts))
 
     out = {
         "metric": "fq_linear_tops_m8192_llama7b_shapes",

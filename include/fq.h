@@ -178,9 +178,11 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
 /* ---------------------------------------------------------------------------------------------
  * fq_gemm_select — tuning hook for benchmarks: force the kernel variant used by fq_gemm_i8 /
  * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
- *   0: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, barrier before the last
- *      k-slice of a stage (the large-problem kernel)
- *   1: as 0 with the barrier at the end of the stage
+ *   7: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the
+ *      two waves of a SIMD alternate LDS-read and MFMA phases (the large-problem kernel)
+ *   8: as 7 with one k-slice per phase
+ *   0: as 7 with LDS reads interleaved between the MFMAs and one barrier per stage, placed before the
+ *      stage's last k-slice          1: as 0 with the barrier at the end of the stage
  *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)
  *   3: as 0 with 64-byte k-stages        4: as 0 with 4 waves (128x128 per wave)
  *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies

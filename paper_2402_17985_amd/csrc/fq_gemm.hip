@@ -270,7 +270,7 @@ __device__ __forceinline__ void mfma_slice(const v4i (&a)[FM], const v4i (&b)[FN
 // =============================================================================================
 // gemm_dma_kernel: direct global -> LDS stages, register double-buffered MFMA operands
 // =============================================================================================
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
 __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                               const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                               const float* __restrict__ s_x, const float* __restrict__ s_w,
@@ -418,7 +418,96 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
         }
     };
 
-    if constexpr (PIPE == 0) {
+    if constexpr (PIPE == 2) {
+        // ---- ping-pong.  The 8 waves form two groups (waves 0-3 and 4-7; wave w and w+4 share a SIMD).
+        //      Every wave alternates a memory phase (LDS operand reads of SPP k-slices, for INT4 also
+        //      the widening to int8, and once per stage the DMA of a later stage) and a compute phase
+        //      (the MFMAs on those operands), with a workgroup barrier after each phase.  Group B runs
+        //      one barrier interval behind group A, so on every SIMD one wave issues nothing but MFMAs
+        //      while its partner issues nothing but memory instructions.
+        //
+        //      Barrier events e = 1, 2, ...; L = 2 * NPH * nk loop barriers per wave.  Group A passes its
+        //      loop barriers at e = 1..L and one balancing barrier at e = L+1; group B one staggering
+        //      barrier at e = 1 and its loop barriers at e = 2..L+1.  Buffer of stage t-1 is last read
+        //      in B's final memory phase of stage t-1, which ends at e = 2 NPH t; A issues the DMA of
+        //      stage t+1 into it in its first memory phase of stage t, which begins after that event
+        //      (B later still).  Stage t+1 is first read by A after e = 2 NPH (t+1); A waits for its own
+        //      DMA before that barrier (end of its last compute phase of stage t), B before the barrier
+        //      closing its last memory phase of stage t, which is the same event. ----
+        static_assert(PIPE != 2 || (NSTAGE == 2 && NW == 8), "ping-pong pipeline: 8 waves, 2 buffers");
+        constexpr int SPP = (MODE == MODE_I4) ? 1 : PP_SLICES;     // packed k-slices per phase
+        constexpr int NPH = KS / SPP;
+        constexpr int NOP = (MODE == MODE_I4) ? 2 * SPP : SPP;     // operand sets (MFMA k-steps) per phase
+        static_assert(KS % SPP == 0, "phases must tile the stage");
+        const bool group_b = wave >= 4;
+        v4i pa[NOP][FM], pb[NOP][FN];
+
+        issue_any(0);
+        if (nk > 1) issue_any(1);
+        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        if (group_b) __builtin_amdgcn_s_barrier();
+        for (int kt = 0; kt < nk; ++kt) {
+            const uint8_t* s = smem + (kt & 1) * STAGE;
+#pragma unroll
+            for (int ph = 0; ph < NPH; ++ph) {
+                // ---------------- memory phase ----------------
+                if (ph == 0 && kt >= 1 && kt + 1 < nk) issue_any(kt + 1);
+#pragma unroll
+                for (int q = 0; q < SPP; ++q) {
+                    const int ks = ph * SPP + q;
+                    v4i ra[FM], rb[FN];
+#pragma unroll
+                    for (int i = 0; i < FM; ++i) ra[i] = *reinterpret_cast<const v4i*>(s + a_rd + i * 32 * BKB + kofs[ks]);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) rb[j] = *reinterpret_cast<const v4i*>(s + b_rd + j * 32 * BKB + kofs[ks]);
+                    if constexpr (MODE == MODE_I4) {
+#pragma unroll
+                        for (int i = 0; i < FM; ++i) {
+                            pa[2 * q][i] = (ra[i] << 4) & (int)0xf0f0f0f0;
+                            pa[2 * q + 1][i] = ra[i] & (int)0xf0f0f0f0;
+                        }
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            pb[2 * q][j] = (rb[j] << 4) & (int)0xf0f0f0f0;
+                            pb[2 * q + 1][j] = rb[j] & (int)0xf0f0f0f0;
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < FM; ++i) pa[q][i] = ra[i];
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) pb[q][j] = rb[j];
+                    }
+                }
+                if (ph == NPH - 1 && group_b) __builtin_amdgcn_s_waitcnt(0x0070);   // B: my DMA of stage kt+1 landed
+                else __builtin_amdgcn_s_waitcnt(0xc07f);                            // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                // ---------------- compute phase ----------------
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int o = 0; o < NOP; ++o)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            if constexpr (MODE == MODE_BF16)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, pb[o][j]),
+                                                                                   __builtin_bit_cast(v8bf, pa[o][i]),
+                                                                                   acc[i][j], 0, 0, 0);
+                            else
+                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[o][j], pa[o][i], acc[i][j], 0, 0, 0);
+                        }
+                __builtin_amdgcn_s_setprio(0);
+                if (ph == NPH - 1 && !group_b) __builtin_amdgcn_s_waitcnt(0x0f70);  // A: my DMA of stage kt+1 landed
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (!group_b) __builtin_amdgcn_s_barrier();
+    } else if constexpr (PIPE == 0) {
         // ---- end-of-stage barrier, NSTAGE buffers: NSTAGE-1 stages in flight ----
 #pragma unroll
         for (int st = 0; st < NSTAGE - 1; ++st)
@@ -482,7 +571,7 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
 // last, partly filled round of at most half the CUs, those tiles are instead computed as two
 // (BM/2) x BN halves by workgroups [n_main, n_main + 2 * n_tail), so that the last round takes about
 // half as long.
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __restrict__ A,
                                                                 const uint8_t* __restrict__ B, int M, int N,
                                                                 int rowbytes, const float* __restrict__ s_x,
@@ -495,13 +584,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
     int tile_m, tile_n;
     if (wg < n_main) {
         tile_of_workgroup(wg, n_main, tiles_m, tiles_n, tile_m, tile_n);
-        gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
+        gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
                                                                 s_x, s_w, Y, y_dtype, ldy);
     } else {
         if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
             const int t = wg - n_main;
             tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
-            gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE>(smem, tile_m * BM + (t & 1) * (BM / 2),
+            gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM + (t & 1) * (BM / 2),
                                                                         tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
                                                                         Y, y_dtype, ldy);
         }
@@ -642,14 +731,14 @@ int compute_units()
     return cus;
 }
 
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
 int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                void* Y, int y_dtype, int ldy, hipStream_t stream)
 {
     // the DMA kernel addresses rows with 32-bit byte offsets
     if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
         return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
-    auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE>;
+    auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>;
     constexpr int smem = NSTAGE * (BM + BN) * BKB;
     static bool attr_set = false;
     if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
@@ -692,7 +781,7 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
     return FQ_OK;
 }
 
-constexpr int NUM_VARIANTS = 7;
+constexpr int NUM_VARIANTS = 9;
 
 template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
@@ -701,7 +790,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     int v = g_variant;
     if (v < 0) {
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-        v = (big_tiles >= 192) ? 0 : 2;
+        v = (big_tiles >= 192) ? 7 : 2;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
@@ -711,6 +800,8 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }

@@ -109,7 +109,7 @@ def test_device_calls_validate_before_launching():
     assert L.fq_flatten_quant_act(*args(wsb=ws - 1)) == 7
     assert b"workspace" in L.fq_last_error_string()
     assert L.fq_gemm_bf16(dummy, dummy, 4, 4, 12, dummy, 4, None) == 2
-    assert L.fq_gemm_select(170) == 4
+    assert L.fq_gemm_select(1700) == 4
     assert L.fq_gemm_select(-1) == 0
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 8) >= 8 * 64 + ws
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 4) >= 8 * 32 + ws
