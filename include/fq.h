@@ -180,7 +180,7 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
  *   7: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the
  *      two waves of a SIMD alternate LDS-read and MFMA phases (the large-problem kernel)
- *   8: as 7 with one k-slice per phase
+ *   8: as 7 with one k-slice per phase        9: as 7 with 64-byte k-stages in a ring of 4 buffers
  *   0: as 7 with LDS reads interleaved between the MFMAs and one barrier per stage, placed before the
  *      stage's last k-slice          1: as 0 with the barrier at the end of the stage
  *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)

@@ -434,7 +434,9 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
         //      (B later still).  Stage t+1 is first read by A after e = 2 NPH (t+1); A waits for its own
         //      DMA before that barrier (end of its last compute phase of stage t), B before the barrier
         //      closing its last memory phase of stage t, which is the same event. ----
-        static_assert(PIPE != 2 || (NSTAGE == 2 && NW == 8), "ping-pong pipeline: 8 waves, 2 buffers");
+        //      With more than two buffers, NSTAGE-1 stages are in flight and the waits leave NSTAGE-2 of
+        //      them outstanding (all of them once no further stage is issued).
+        static_assert(PIPE != 2 || NW == 8, "ping-pong pipeline: 8 waves");
         constexpr int SPP = (MODE == MODE_I4) ? 1 : PP_SLICES;     // packed k-slices per phase
         constexpr int NPH = KS / SPP;
         constexpr int NOP = (MODE == MODE_I4) ? 2 * SPP : SPP;     // operand sets (MFMA k-steps) per phase
@@ -442,17 +444,22 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
         const bool group_b = wave >= 4;
         v4i pa[NOP][FM], pb[NOP][FN];
 
-        issue_any(0);
-        if (nk > 1) issue_any(1);
-        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+#pragma unroll
+        for (int st = 0; st < NSTAGE - 1; ++st)
+            if (st < nk) issue_any(st);
+        if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+        else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
         __builtin_amdgcn_s_barrier();
         if (group_b) __builtin_amdgcn_s_barrier();
+        int buf = 0;
         for (int kt = 0; kt < nk; ++kt) {
-            const uint8_t* s = smem + (kt & 1) * STAGE;
+            const uint8_t* s = smem + buf * STAGE;
+            buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
+            const bool steady = kt + NSTAGE - 1 < nk;
 #pragma unroll
             for (int ph = 0; ph < NPH; ++ph) {
                 // ---------------- memory phase ----------------
-                if (ph == 0 && kt >= 1 && kt + 1 < nk) issue_any(kt + 1);
+                if (ph == 0 && steady) issue_any(kt + NSTAGE - 1);
 #pragma unroll
                 for (int q = 0; q < SPP; ++q) {
                     const int ks = ph * SPP + q;
@@ -479,8 +486,11 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
                         for (int j = 0; j < FN; ++j) pb[q][j] = rb[j];
                     }
                 }
-                if (ph == NPH - 1 && group_b) __builtin_amdgcn_s_waitcnt(0x0070);   // B: my DMA of stage kt+1 landed
-                else __builtin_amdgcn_s_waitcnt(0xc07f);                            // lgkmcnt(0)
+                __builtin_amdgcn_s_waitcnt(0xc07f);                                 // lgkmcnt(0)
+                if (ph == NPH - 1 && group_b) {                                     // B: my DMA of stage kt+1 landed
+                    if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+                    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
@@ -500,7 +510,10 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
                                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[o][j], pa[o][i], acc[i][j], 0, 0, 0);
                         }
                 __builtin_amdgcn_s_setprio(0);
-                if (ph == NPH - 1 && !group_b) __builtin_amdgcn_s_waitcnt(0x0f70);  // A: my DMA of stage kt+1 landed
+                if (ph == NPH - 1 && !group_b) {                                    // A: my DMA of stage kt+1 landed
+                    if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+                    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
@@ -781,7 +794,7 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
     return FQ_OK;
 }
 
-constexpr int NUM_VARIANTS = 9;
+constexpr int NUM_VARIANTS = 10;
 
 template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
@@ -802,6 +815,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }

@@ -155,7 +155,7 @@ def _gemm_acc(Xq, Wq, bits):
     return Y.cpu().numpy()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_gemm_accumulators_bit_exact(variant, bits):
     rng = np.random.default_rng(100 * variant + bits)
