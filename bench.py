@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of the dominant kernel (INT4 GEMM, average of its two launches per step) for
 # the default workload and kernel choice, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
 # by a plain 1 GiB copy in the same runs: profiles/pmc_traffic_bench_cfg3_m8192.txt.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.13e8}
+MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.23e8}
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (INT4 is widened to int8 on chip: same ceiling)
 BF16_PEAK_TFLOPS = 2500.0
@@ -91,14 +91,20 @@ def main():
             t0 = time.time()
             L = WL.make_layer(cfg, li)
             sp = L.spec
-            Xd = torch.from_numpy(L.X_store.view(np.int16)).to(dev).view(torch.bfloat16)
-            Wd = torch.from_numpy(L.W_store.view(np.int16)).to(dev).view(torch.bfloat16)
+            def upload(store, dtype):
+                if dtype == "bf16":
+                    return torch.from_numpy(store.view(np.int16)).to(dev).view(torch.bfloat16)
+                return torch.from_numpy(store).to(dev)
+            Xd, Wd = upload(L.X_store, sp.x_dtype), upload(L.W_store, sp.w_dtype)
             lay = fq.FqLinear(Wd, L.chmax, L.T, sp.bits, device=dev, align=args.align)
             Y = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             Ybf = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             a_static = torch.tensor([L.T], dtype=torch.float32, device=dev) if args.static else None
             lay.workspace(sp.M)
-            layers.append(dict(name=f"{cname}.{sp.name}", spec=sp, L=L, X=Xd, W=Wd, lay=lay, Y=Y, Ybf=Ybf,
+            # operands of the bf16 baseline GEMM (the tensors themselves when they already are bf16)
+            Xb = Xd if Xd.dtype == torch.bfloat16 else Xd.to(torch.bfloat16)
+            Wb = Wd if Wd.dtype == torch.bfloat16 else Wd.to(torch.bfloat16)
+            layers.append(dict(name=f"{cname}.{sp.name}", spec=sp, L=L, X=Xd, W=Wd, Xb=Xb, Wb=Wb, lay=lay, Y=Y, Ybf=Ybf,
                                a_static=a_static))
             log(f"[setup] {cname}.{sp.name}: M={sp.M} K={sp.K} N={sp.N} bits={sp.bits} T={L.T:.4g} "
                 f"Kprime={lay.Kprime} Kpad={lay.Kpad} (+{100.0 * (lay.Kpad - sp.K) / sp.K:.1f}%) "
@@ -152,7 +158,7 @@ def main():
         gemm = fq.fq_gemm_i8 if sp.bits == 8 else fq.fq_gemm_i4
         f_gemm = lambda: gemm(Xq, lay.Wq, s_x, lay.s_w, d["Y"])
         f_lin = lambda: lay.forward(d["X"], Y=d["Y"], absmax_in=d["a_static"])
-        f_bf = lambda: fq.fq_gemm_bf16(d["X"], d["W"], d["Ybf"])
+        f_bf = lambda: fq.fq_gemm_bf16(d["Xb"], d["Wb"], d["Ybf"])
         t_act = event_time_ms(torch, f_act, args.steps)
         t_gemm = event_time_ms(torch, f_gemm, args.steps)
         t_lin = event_time_ms(torch, f_lin, args.steps)
@@ -160,7 +166,7 @@ def main():
         t_bf16_total += t_bf
         flops = 2.0 * sp.M * Kpad * sp.N
         # algorithmic HBM bytes of flatten-quantize: X read once (static) or twice (dynamic), Xq written
-        act_bytes = sp.M * sp.K * 2 * (1 if args.static else 2) + sp.M * cols
+        act_bytes = sp.M * sp.K * d["X"].element_size() * (1 if args.static else 2) + sp.M * cols
         if sp.bits == dom_bits:
             dom["flops"] += flops
             dom["ms"] += t_gemm
@@ -189,7 +195,7 @@ def main():
         del Xq, ws
     dom_avg_ms = dom["ms"] / dom["launches"]
     dom_achieved = dom["flops"] / dom["launches"] / dom_avg_ms / 1e9          # TOPS
-    roofline = dict(bound="mfma", kernel=f"gemm_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
+    roofline = dict(bound="mfma", kernel=f"gemm_dma_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
                     peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4),
                     traffic=MEASURED_TRAFFIC_BYTES.get((args.configs, args.variant, args.align)),
                     avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])

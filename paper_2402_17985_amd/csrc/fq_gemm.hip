@@ -803,7 +803,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     int v = g_variant;
     if (v < 0) {
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-        v = (big_tiles >= 192) ? 7 : 2;
+        v = (big_tiles >= 192) ? 7 : 6;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
