@@ -402,3 +402,80 @@ int fqo_linear(const float *X, int M, int K, int ldx, const int32_t *src, const 
     free(Xq);
     return rc;
 }
+
+/* ==========================================================================================
+ * Offline policy helpers of the paper (host side; they only produce the hot path's inputs).
+ * ======================================================================================== */
+
+/* linear-interpolation quantile of a sorted array (position q*(n-1)); the paper only says the
+ * quartiles split off the lowest and highest 25 %; this is the reading taken. */
+static double quantile_sorted(const double *v, int n, double q)
+{
+    double pos = q * (double)(n - 1);
+    int lo = (int)floor(pos);
+    int hi = lo + 1 < n ? lo + 1 : lo;
+    double frac = pos - (double)lo;
+    return v[lo] + (v[hi] - v[lo]) * frac;
+}
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Truncation threshold (Sec. 4.2, Eq. 6-7): the channel maxima are clipped to the box-plot
+ * fences [Q1 - 1.5 IQR, Q3 + 1.5 IQR] and T = beta * mean(clipped maxima).  float64, result
+ * rounded to fp32.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_threshold_boxplot(const float *chmax, int K, float beta, float *T_out)
+{
+    if (!chmax || !T_out || K <= 0 || !(beta > 0.0f) || isinf(beta)) return FQO_ERR_ARG;
+    double *v = (double *)malloc((size_t)K * sizeof(double));
+    for (int j = 0; j < K; ++j) {
+        if (!(chmax[j] >= 0.0f) || isinf(chmax[j])) { free(v); return FQO_ERR_ARG; }
+        v[j] = (double)chmax[j];
+    }
+    qsort(v, (size_t)K, sizeof(double), cmp_double);
+    double q1 = quantile_sorted(v, K, 0.25), q3 = quantile_sorted(v, K, 0.75);
+    double iqr = q3 - q1, lo = q1 - 1.5 * iqr, hi = q3 + 1.5 * iqr;
+    double sum = 0.0;
+    for (int j = 0; j < K; ++j) {
+        double c = v[j];
+        if (c < lo) c = lo;
+        if (c > hi) c = hi;
+        sum += c;
+    }
+    free(v);
+    *T_out = (float)((double)beta * (sum / (double)K));
+    return FQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Channel smoothing factors (Sec. 4.2, Eq. 5):
+ *   s_j = Sigmoid((max|X_j| - mu) / sigma)^alpha / Sigmoid((max|W_j| - mu) / sigma)^(1 - alpha)
+ * with mu and sigma the mean and (population) standard deviation of the activation channel
+ * maxima, as printed (the weight term is normalized with the same mu and sigma).
+ * The smoothed operands are X diag(s)^-1 and diag(s) W.  sigma = 0 (all maxima equal) gives
+ * s_j = 1.  float64, results rounded to fp32.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_smooth_scales(const float *chmax_x, const float *chmax_w, int K, float alpha, float *s_out)
+{
+    if (!chmax_x || !chmax_w || !s_out || K <= 0 || !(alpha >= 0.0f) || !(alpha <= 1.0f)) return FQO_ERR_ARG;
+    double mu = 0.0;
+    for (int j = 0; j < K; ++j) mu += (double)chmax_x[j];
+    mu /= (double)K;
+    double var = 0.0;
+    for (int j = 0; j < K; ++j) {
+        double d = (double)chmax_x[j] - mu;
+        var += d * d;
+    }
+    double sigma = sqrt(var / (double)K);
+    for (int j = 0; j < K; ++j) {
+        if (sigma == 0.0) { s_out[j] = 1.0f; continue; }
+        double zx = ((double)chmax_x[j] - mu) / sigma, zw = ((double)chmax_w[j] - mu) / sigma;
+        double sx = 1.0 / (1.0 + exp(-zx)), sw = 1.0 / (1.0 + exp(-zw));
+        s_out[j] = (float)(pow(sx, (double)alpha) / pow(sw, 1.0 - (double)alpha));
+    }
+    return FQO_OK;
+}

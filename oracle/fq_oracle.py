@@ -232,3 +232,23 @@ def linear(X, src, rep, Wq, s_w, bits, a_static=None, row0=0, rows=None, want_y=
                           ctypes.byref(s_x))
     _check(rc, "fqo_linear")
     return acc, y, np.float32(s_x.value)
+
+
+def threshold_boxplot(chmax, beta=1.3) -> np.float32:
+    """Eq. 6-7: box-plot clipped mean of the channel maxima times beta."""
+    chmax = _f32(chmax)
+    T = ctypes.c_float(0)
+    rc = lib().fqo_threshold_boxplot(_p(chmax, ctypes.c_float), chmax.shape[0], ctypes.c_float(beta), ctypes.byref(T))
+    _check(rc, "fqo_threshold_boxplot")
+    return np.float32(T.value)
+
+
+def smooth_scales(chmax_x, chmax_w, alpha=0.5):
+    """Eq. 5: per-channel smoothing factors s (X / s, s * W)."""
+    chmax_x, chmax_w = _f32(chmax_x), _f32(chmax_w)
+    assert chmax_x.shape == chmax_w.shape
+    out = np.empty(chmax_x.shape[0], dtype=np.float32)
+    rc = lib().fqo_smooth_scales(_p(chmax_x, ctypes.c_float), _p(chmax_w, ctypes.c_float), chmax_x.shape[0],
+                                 ctypes.c_float(alpha), _p(out, ctypes.c_float))
+    _check(rc, "fqo_smooth_scales")
+    return out
