@@ -92,6 +92,32 @@ int fq_flatten_plan(const float* chmax_host, int K, float T, int align,
                     int* Kprime_out, int* Kpad_out);
 
 /* ---------------------------------------------------------------------------------------------
+ * fq_channel_absmax, fq_threshold_boxplot, fq_smooth_scales — the paper's offline policy for the
+ * plan's inputs.  The latter two are HOST functions.
+ *
+ * fq_threshold_boxplot (Sec. 4.2 Eq. 6-7): the channel maxima are clipped to the box-plot fences
+ *   [Q1 - 1.5 IQR, Q3 + 1.5 IQR] (quartiles by linear interpolation) and
+ *   T = beta * mean(clipped maxima); the paper uses beta = 1.3.  chmax_host [K] >= 0, finite.
+ * fq_smooth_scales (Sec. 4.2 Eq. 5):
+ *   s_j = Sigmoid((max|X_j| - mu)/sigma)^alpha / Sigmoid((max|W_j| - mu)/sigma)^(1 - alpha),
+ *   mu / sigma = mean / population standard deviation of the activation channel maxima (the weight
+ *   term uses the same mu and sigma, as printed); alpha in [0, 1], the paper uses 0.5.  The smoothed
+ *   layer is X diag(s)^-1 and diag(s) W (to be folded into the producer of X and into W offline).
+ *   sigma = 0 gives s_j = 1.  chmax_w_host[j] = max_n |W[n, j]|.
+ * Both evaluate in float64 and round the results to fp32.
+ * ------------------------------------------------------------------------------------------- */
+/* fq_channel_absmax — calibration statistic on the device (Sec. 4.2: the per-channel maxima that
+ *   Eq. 2, Eq. 5 and Eq. 6 consume).  chmax_dev[j] = max(start_j, max_i |X[i, j]|) with start_j = 0,
+ *   or, with accumulate != 0, the value chmax_dev[j] holds on entry (a running maximum over
+ *   calibration batches; it must be a non-negative, non-NaN fp32).  NaN elements of X are ignored.
+ *   X [M, K] DEVICE, F32 / F16 / BF16, row stride ldx elements (ldx * element size a multiple of 16,
+ *   X 16-byte aligned); chmax_dev fp32 [K] DEVICE; asynchronous on `stream`; no workspace. */
+int fq_channel_absmax(const void* X, int x_dtype, int M, int K, int ldx, int accumulate, float* chmax_dev,
+                      void* stream);
+int fq_threshold_boxplot(const float* chmax_host, int K, float beta, float* T_out_host);
+int fq_smooth_scales(const float* chmax_x_host, const float* chmax_w_host, int K, float alpha, float* s_out_host);
+
+/* ---------------------------------------------------------------------------------------------
  * fq_flatten_weights — offline: quantize W per tensor and repeat its channels by the map.
  * Eq. 1 (s_w = max|W| / qmax, qmax = 2^(bits-1) - 1), Eq. 4 (repeat), done "during model
  * quantization" (Fig. 3).

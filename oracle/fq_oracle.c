@@ -479,3 +479,22 @@ int fqo_smooth_scales(const float *chmax_x, const float *chmax_w, int K, float a
     }
     return FQO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Calibration statistic (Sec. 4.2: the channel maxima that Eq. 2, Eq. 5 and Eq. 6 consume):
+ *   chmax[j] = max(prev[j], max_i |x[i, j]|), prev = 0 when accumulate == 0, else the values
+ * chmax holds on entry (a running maximum over calibration batches).
+ * ---------------------------------------------------------------------------------------- */
+int fqo_channel_absmax(const float *X, int M, int K, int ldx, int accumulate, float *chmax)
+{
+    if (!X || !chmax || M <= 0 || K <= 0 || ldx < K) return FQO_ERR_ARG;
+    for (int j = 0; j < K; ++j) {
+        float m = accumulate ? chmax[j] : 0.0f;
+        for (int i = 0; i < M; ++i) {
+            float t = fabsf(X[(size_t)i * ldx + j]);
+            if (t > m) m = t;
+        }
+        chmax[j] = m;
+    }
+    return FQO_OK;
+}

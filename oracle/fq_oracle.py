@@ -252,3 +252,13 @@ def smooth_scales(chmax_x, chmax_w, alpha=0.5):
                                  ctypes.c_float(alpha), _p(out, ctypes.c_float))
     _check(rc, "fqo_smooth_scales")
     return out
+
+
+def channel_absmax(X, prev=None):
+    """Per-channel max |x| of X [M, K]; with prev [K] the running maximum max(prev, .)."""
+    X = _f32(X)
+    M, K = X.shape
+    out = np.zeros(K, dtype=np.float32) if prev is None else _f32(prev).copy()
+    rc = lib().fqo_channel_absmax(_p(X, ctypes.c_float), M, K, K, 0 if prev is None else 1, _p(out, ctypes.c_float))
+    _check(rc, "fqo_channel_absmax")
+    return out

@@ -21,7 +21,8 @@ ERR_NAMES = {1: "FQ_ERR_NULL", 2: "FQ_ERR_SHAPE", 3: "FQ_ERR_DTYPE", 4: "FQ_ERR_
 # every entry point include/fq.h declares
 SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_weights",
            "fq_weights_workspace_bytes", "fq_flatten_quant_act", "fq_act_workspace_bytes", "fq_gemm_i8",
-           "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select"]
+           "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
+           "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax"]
 
 
 class FqError(RuntimeError):
@@ -49,6 +50,9 @@ def lib() -> ctypes.CDLL:
     L.fq_gemm_select.argtypes = [c_int]
     L.fq_flatten_plan.argtypes = [vp, c_int, c_float, c_int, vp, vp, c_int, ctypes.POINTER(c_int),
                                   ctypes.POINTER(c_int)]
+    L.fq_threshold_boxplot.argtypes = [vp, c_int, c_float, ctypes.POINTER(c_float)]
+    L.fq_smooth_scales.argtypes = [vp, vp, c_int, c_float, vp]
+    L.fq_channel_absmax.argtypes = [vp, c_int, c_int, c_int, c_int, c_int, vp, vp]
     L.fq_flatten_weights.argtypes = [vp, c_int, c_int, c_int, c_int, vp, c_int, c_int, vp, vp, vp, c_size_t, vp]
     L.fq_weights_workspace_bytes.restype = c_size_t
     L.fq_weights_workspace_bytes.argtypes = [c_int, c_int]
@@ -124,6 +128,35 @@ def fq_flatten_plan(chmax: np.ndarray, T: float, align: int = 32) -> Tuple[np.nd
     _check(lib().fq_flatten_plan(chmax.ctypes.data, K, T, align, src.ctypes.data, rep.ctypes.data, kpad.value,
                                  ctypes.byref(kp), ctypes.byref(kpad)))
     return src, rep, kp.value, kpad.value
+
+
+def fq_threshold_boxplot(chmax: np.ndarray, beta: float = 1.3) -> float:
+    """Host call (Eq. 6-7).  Returns T as a Python float holding an fp32 value."""
+    chmax = np.ascontiguousarray(chmax, dtype=np.float32)
+    T = ctypes.c_float(0)
+    _check(lib().fq_threshold_boxplot(chmax.ctypes.data, chmax.shape[0], beta, ctypes.byref(T)))
+    return float(T.value)
+
+
+def fq_smooth_scales(chmax_x: np.ndarray, chmax_w: np.ndarray, alpha: float = 0.5) -> np.ndarray:
+    """Host call (Eq. 5).  Returns the fp32 smoothing factors s [K]."""
+    chmax_x = np.ascontiguousarray(chmax_x, dtype=np.float32)
+    chmax_w = np.ascontiguousarray(chmax_w, dtype=np.float32)
+    if chmax_x.shape != chmax_w.shape:
+        raise ValueError("chmax_x and chmax_w must have the same length")
+    out = np.empty(chmax_x.shape[0], dtype=np.float32)
+    _check(lib().fq_smooth_scales(chmax_x.ctypes.data, chmax_w.ctypes.data, chmax_x.shape[0], alpha, out.ctypes.data))
+    return out
+
+
+def fq_channel_absmax(X, chmax, accumulate: bool = False, stream=None) -> None:
+    """chmax (fp32 [K], device) = per-channel max |X|, or the running maximum when accumulate is set."""
+    _dev2d(X, "X")
+    M, K = X.shape
+    if chmax.numel() != K or _dtype_code(chmax) != FQ_F32 or not chmax.is_contiguous():
+        raise ValueError("chmax must be a contiguous fp32 tensor of K elements")
+    _check(lib().fq_channel_absmax(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), int(bool(accumulate)),
+                                   chmax.data_ptr(), _stream(stream)))
 
 
 def fq_weights_workspace_bytes(K: int, Kpad: int) -> int:

@@ -1,6 +1,8 @@
 // C-ABI layer of libfq: argument validation, the host-side flatten plan, and the composition
 // of the kernels into the calls declared in include/fq.h.  Nothing here allocates or synchronizes.
+#include <algorithm>
 #include <cmath>
+#include <vector>
 #include <cstdarg>
 #include <cstdio>
 
@@ -124,6 +126,70 @@ int fq_flatten_plan(const float* chmax_host, int K, float T, int align, int32_t*
         rep_host[tail] = 0;
     }
     return FQ_OK;
+}
+
+int fq_threshold_boxplot(const float* chmax_host, int K, float beta, float* T_out_host)
+{
+    clear_error();
+    if (!chmax_host || !T_out_host) return fail(FQ_ERR_NULL, "chmax or T_out is NULL");
+    if (K <= 0) return fail(FQ_ERR_SHAPE, "K = %d", K);
+    if (!(beta > 0.0f) || std::isinf(beta)) return fail(FQ_ERR_RANGE, "beta = %g must be positive and finite", (double)beta);
+    std::vector<double> v(chmax_host, chmax_host + K);
+    for (int j = 0; j < K; ++j)
+        if (!(v[j] >= 0.0) || std::isinf(v[j])) return fail(FQ_ERR_RANGE, "chmax[%d] = %g must be finite and >= 0", j, v[j]);
+    std::sort(v.begin(), v.end());
+    // quartiles by linear interpolation at position q * (K - 1)
+    auto quartile = [&](double q) {
+        const double pos = q * (double)(K - 1);
+        const int lo = (int)std::floor(pos), hi = std::min(lo + 1, K - 1);
+        return v[lo] + (v[hi] - v[lo]) * (pos - (double)lo);
+    };
+    const double q1 = quartile(0.25), q3 = quartile(0.75);
+    const double fence_lo = q1 - 1.5 * (q3 - q1), fence_hi = q3 + 1.5 * (q3 - q1);
+    double sum = 0.0;
+    for (int j = 0; j < K; ++j) sum += std::min(std::max(v[j], fence_lo), fence_hi);
+    *T_out_host = (float)((double)beta * (sum / (double)K));
+    return FQ_OK;
+}
+
+int fq_smooth_scales(const float* chmax_x_host, const float* chmax_w_host, int K, float alpha, float* s_out_host)
+{
+    clear_error();
+    if (!chmax_x_host || !chmax_w_host || !s_out_host) return fail(FQ_ERR_NULL, "chmax_x, chmax_w or s_out is NULL");
+    if (K <= 0) return fail(FQ_ERR_SHAPE, "K = %d", K);
+    if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return fail(FQ_ERR_RANGE, "alpha = %g must lie in [0, 1]", (double)alpha);
+    double mean = 0.0;
+    for (int j = 0; j < K; ++j) {
+        const float a = chmax_x_host[j], b = chmax_w_host[j];
+        if (!(a >= 0.0f) || std::isinf(a) || !(b >= 0.0f) || std::isinf(b))
+            return fail(FQ_ERR_RANGE, "channel maximum %d must be finite and >= 0", j);
+        mean += (double)a;
+    }
+    mean /= (double)K;
+    double ss = 0.0;
+    for (int j = 0; j < K; ++j) ss += ((double)chmax_x_host[j] - mean) * ((double)chmax_x_host[j] - mean);
+    const double sd = std::sqrt(ss / (double)K);
+    const double a = (double)alpha;
+    for (int j = 0; j < K; ++j) {
+        if (sd == 0.0) {
+            s_out_host[j] = 1.0f;
+            continue;
+        }
+        const double gx = 1.0 / (1.0 + std::exp(-((double)chmax_x_host[j] - mean) / sd));
+        const double gw = 1.0 / (1.0 + std::exp(-((double)chmax_w_host[j] - mean) / sd));
+        s_out_host[j] = (float)(std::pow(gx, a) / std::pow(gw, 1.0 - a));
+    }
+    return FQ_OK;
+}
+
+int fq_channel_absmax(const void* X, int x_dtype, int M, int K, int ldx, int accumulate, float* chmax_dev,
+                      void* stream)
+{
+    clear_error();
+    if (int rc = check_matrix("X", X, x_dtype, M, K, ldx)) return rc;
+    if (!chmax_dev) return fail(FQ_ERR_NULL, "chmax is NULL");
+    if ((reinterpret_cast<uintptr_t>(chmax_dev) & 3u) != 0) return fail(FQ_ERR_ALIGN, "chmax is not 4-byte aligned");
+    return launch_channel_absmax(X, x_dtype, M, K, ldx, accumulate, chmax_dev, static_cast<hipStream_t>(stream));
 }
 
 size_t fq_act_workspace_bytes(int K, int Kpad)

@@ -41,6 +41,10 @@ int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld,
                          int mode, const float* absmax_in, void* out, float* scale_out,
                          const ActWorkspace& ws, hipStream_t stream);
 
+// chmax[j] = max(start, max_i |X[i, j]|), start = 0 or (accumulate) the non-negative value held on entry
+int launch_channel_absmax(const void* X, int x_dtype, int M, int K, int ld, int accumulate, float* chmax,
+                          hipStream_t stream);
+
 int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits,
                     const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
                     hipStream_t stream);

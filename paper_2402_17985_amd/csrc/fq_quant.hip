@@ -335,25 +335,31 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     }
 }
 
+// Per input channel max|x| into cmax (fp32 bit patterns, which order like the non-negative floats
+// they hold); accumulate keeps what cmax holds on entry as the starting value.
+template <int DT>
+void launch_colabsmax(const void* X, int M, int K, int ld, bool accumulate, uint32_t* cmax, hipStream_t stream)
+{
+    constexpr int VEC = Elem<DT>::VEC;
+    if (!accumulate) fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(cmax, K, 0u);
+    const int bx = (K + 64 * VEC - 1) / (64 * VEC);
+    // a workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves); aim at
+    // about 1024 workgroups, at most 512 rows each
+    long long rpb = ((long long)M * bx + 1023) / 1024;
+    rpb = (rpb + 63) / 64 * 64;
+    if (rpb < 128) rpb = 128;
+    if (rpb > 512) rpb = 512;
+    dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
+    colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, cmax);
+}
+
 template <int DT>
 int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx, const int32_t* rep,
                      int Kpad, int bits, int mode, const float* absmax_in, void* out, float* scale_out,
                      const ActWorkspace& ws, hipStream_t stream)
 {
-    constexpr int VEC = Elem<DT>::VEC;
     const int qmax = (1 << (bits - 1)) - 1;
-    if (mode != 1) {
-        fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(ws.cmax, K, 0u);
-        const int bx = (K + 64 * VEC - 1) / (64 * VEC);
-        // a workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves); aim at
-        // about 1024 workgroups, at most 512 rows each
-        long long rpb = ((long long)M * bx + 1023) / 1024;
-        rpb = (rpb + 63) / 64 * 64;
-        if (rpb < 128) rpb = 128;
-        if (rpb > 512) rpb = 512;
-        dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
-        colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, ws.cmax);
-    }
+    if (mode != 1) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
                                          scale_out, ws.scalars);
     const int G = Kpad / 16;
@@ -404,6 +410,21 @@ int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld, const
     default:
         return fail(FQ_ERR_DTYPE, "unsupported input dtype %d", x_dtype);
     }
+}
+
+int launch_channel_absmax(const void* X, int x_dtype, int M, int K, int ld, int accumulate, float* chmax,
+                          hipStream_t stream)
+{
+    uint32_t* cmax = reinterpret_cast<uint32_t*>(chmax);
+    switch (x_dtype) {
+    case FQ_F32: launch_colabsmax<FQ_F32>(X, M, K, ld, accumulate != 0, cmax, stream); break;
+    case FQ_F16: launch_colabsmax<FQ_F16>(X, M, K, ld, accumulate != 0, cmax, stream); break;
+    case FQ_BF16: launch_colabsmax<FQ_BF16>(X, M, K, ld, accumulate != 0, cmax, stream); break;
+    default: return fail(FQ_ERR_DTYPE, "unsupported input dtype %d", x_dtype);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "channel absmax launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
 }
 
 }  // namespace fq

@@ -113,3 +113,24 @@ def test_device_calls_validate_before_launching():
     assert L.fq_gemm_select(-1) == 0
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 8) >= 8 * 64 + ws
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 4) >= 8 * 32 + ws
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_policy_helpers_match_oracle(seed):
+    """Threshold (Eq. 6-7) and smoothing factors (Eq. 5): host functions of the library against the oracle."""
+    rng = np.random.default_rng(seed)
+    K = int(rng.integers(3, 2000))
+    cx = (np.abs(rng.standard_normal(K)) * 4).astype(np.float32)
+    cx[rng.integers(0, K, max(1, K // 100))] *= np.float32(rng.uniform(10, 100))
+    cw = (np.abs(rng.standard_normal(K)) * 0.1 + 0.05).astype(np.float32)
+    T = fq.fq_threshold_boxplot(cx, 1.3)
+    assert abs(T - float(O.threshold_boxplot(cx, 1.3))) <= 1e-6 * T
+    s = fq.fq_smooth_scales(cx, cw, 0.5)
+    np.testing.assert_allclose(s, O.smooth_scales(cx, cw, 0.5), rtol=1e-6)
+    # the hand cases of the oracle's pins
+    assert fq.fq_threshold_boxplot(np.array([1, 2, 3, 4, 100], np.float32), 1.3) == float(np.float32(4.42))
+    assert fq.fq_smooth_scales(np.array([5, 5], np.float32), np.array([1, 2], np.float32)).tolist() == [1.0, 1.0]
+    with pytest.raises(fq.FqError):
+        fq.fq_threshold_boxplot(cx, -1.0)
+    with pytest.raises(fq.FqError):
+        fq.fq_smooth_scales(cx, cw, 2.0)

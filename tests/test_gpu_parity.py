@@ -261,3 +261,43 @@ def test_gemm_bf16_baseline(variant):
     ref = Xf.astype(np.float64) @ Wf.astype(np.float64).T
     # fp32 accumulation of K = 1032 products, then one bf16 rounding
     assert rel_err(bf16_to_f64(Y), ref).max() <= 2.0 ** -8 + 1e-4
+
+
+# ------------------------------------------------------------------------------------------
+# calibration statistic and the paper's threshold rule on top of it
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,over", [
+    ("cfg1", {}),
+    ("cfg2", dict(M_override=333, K_override=1000, N_override=8)),
+    ("cfg3", dict(M_override=1100, K_override=4096, N_override=8)),
+    ("cfg4", dict(M_override=70, K_override=5120, N_override=8)),
+])
+def test_channel_absmax_and_boxplot_threshold(cfg, over):
+    """fq_channel_absmax bit-exact against the oracle (one batch, then a second batch accumulated),
+    and Eq. 6-7 on its result gives the oracle's threshold and plan."""
+    L = _layer(cfg, **over)
+    if L.spec.x_dtype != "f32" and L.X.shape[1] % 8:
+        pytest.skip("row stride must be a multiple of 16 bytes")
+    M, K = L.X.shape
+    Xd = to_dev(L.X_store, L.spec.x_dtype)
+    ch = torch.full((K,), 123.0, dtype=torch.float32, device=DEV)       # stale contents must be overwritten
+    half = max(1, M // 2)
+    fq.fq_channel_absmax(Xd[:half], ch)
+    torch.cuda.synchronize()
+    ref1 = O.channel_absmax(L.X[:half])
+    np.testing.assert_array_equal(ch.cpu().numpy(), ref1)
+    if half < M:
+        fq.fq_channel_absmax(Xd[half:], ch, accumulate=True)
+        torch.cuda.synchronize()
+    ref = O.channel_absmax(L.X[half:], prev=ref1) if half < M else ref1
+    got = ch.cpu().numpy()
+    np.testing.assert_array_equal(got, ref)
+    np.testing.assert_array_equal(ref, np.abs(L.X).max(axis=0))
+    T = fq.fq_threshold_boxplot(got, 1.3)
+    T_ref = float(O.threshold_boxplot(ref, 1.3))
+    assert abs(T - T_ref) <= 1e-6 * T_ref
+    src, rep, kp, kpad = fq.fq_flatten_plan(got, T_ref)
+    src_o, rep_o, kp_o, kpad_o = O.plan(ref, T_ref)
+    assert (kp, kpad) == (kp_o, kpad_o)
+    np.testing.assert_array_equal(src, src_o)
+    np.testing.assert_array_equal(rep, rep_o)

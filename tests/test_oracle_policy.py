@@ -76,3 +76,16 @@ def test_policy_bad_arguments():
         O.threshold_boxplot([1, 2], 0.0)
     with pytest.raises(O.OracleError):
         O.smooth_scales([1, 2], [1, 2], 1.5)
+
+
+def test_channel_absmax_hand_case_and_library():
+    """Calibration statistic: hand case, then NumPy's reduction on random data, then the running form."""
+    X = np.array([[1.0, -7.0, 0.0], [-3.0, 2.0, 0.0]], dtype=np.float32)
+    assert O.channel_absmax(X).tolist() == [3.0, 7.0, 0.0]
+    assert O.channel_absmax(X, prev=np.array([5.0, 1.0, 0.5], np.float32)).tolist() == [5.0, 7.0, 0.5]
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((37, 53)).astype(np.float32)
+    B = (rng.standard_normal((11, 53)) * 3).astype(np.float32)
+    np.testing.assert_array_equal(O.channel_absmax(A), np.abs(A).max(axis=0))
+    np.testing.assert_array_equal(O.channel_absmax(B, prev=O.channel_absmax(A)),
+                                  np.abs(np.concatenate([A, B])).max(axis=0))
