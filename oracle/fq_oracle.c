@@ -498,3 +498,28 @@ int fqo_channel_absmax(const float *X, int M, int K, int ldx, int accumulate, fl
     }
     return FQO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Batched integer matrix product (Sec. 5.1, the second quantized operator: the BMM of attention):
+ *   acc[b, i, n] = sum_p Aq[b, i, p] * Bq[b, n, p],  b < batch, dense [batch, M, Kpad] and
+ * [batch, N, Kpad] operands, int32 result (int64 running sum checked against the int32 range).
+ * The paper gives no further detail; per-tensor scales apply to the whole batched tensor, so the
+ * dequantized value is fqo_dequant of this.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_bmm_i32(const int8_t *Aq, const int8_t *Bq, int batch, int M, int N, int Kpad, int32_t *acc_out)
+{
+    if (!Aq || !Bq || !acc_out || batch <= 0 || M <= 0 || N <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int b = 0; b < batch; ++b)
+        for (int i = 0; i < M; ++i)
+            for (int n = 0; n < N; ++n) {
+                const int8_t *x = Aq + ((size_t)b * M + i) * Kpad;
+                const int8_t *w = Bq + ((size_t)b * N + n) * Kpad;
+                int64_t s = 0;
+                for (int p = 0; p < Kpad; ++p) s += (int32_t)x[p] * (int32_t)w[p];
+                if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+                acc_out[((size_t)b * M + i) * N + n] = (int32_t)s;
+            }
+    return bad ? FQO_ERR_OVERFLOW : FQO_OK;
+}

@@ -262,3 +262,16 @@ def channel_absmax(X, prev=None):
     rc = lib().fqo_channel_absmax(_p(X, ctypes.c_float), M, K, K, 0 if prev is None else 1, _p(out, ctypes.c_float))
     _check(rc, "fqo_channel_absmax")
     return out
+
+
+def bmm_i32(Aq, Bq):
+    """acc[b, i, n] = sum_p Aq[b, i, p] * Bq[b, n, p] (int8 operands, int32 result)."""
+    Aq = np.ascontiguousarray(Aq, dtype=np.int8)
+    Bq = np.ascontiguousarray(Bq, dtype=np.int8)
+    batch, M, Kpad = Aq.shape
+    batch2, N, Kpad2 = Bq.shape
+    assert batch == batch2 and Kpad == Kpad2
+    out = np.empty((batch, M, N), dtype=np.int32)
+    rc = lib().fqo_bmm_i32(_p(Aq, ctypes.c_int8), _p(Bq, ctypes.c_int8), batch, M, N, Kpad, _p(out, ctypes.c_int32))
+    _check(rc, "fqo_bmm_i32")
+    return out

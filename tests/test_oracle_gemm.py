@@ -130,3 +130,20 @@ def test_error_shrinks_as_threshold_shrinks():
         _, y, _ = O.linear(L.X, src, rep, Wq, s_w, 8)
         errs.append(np.linalg.norm(y - ref) / np.linalg.norm(ref))
     assert errs[0] > errs[1] > errs[2]
+
+
+def test_bmm_hand_case_and_library():
+    """Batched product (Sec. 5.1): a hand case with distinct batches (a swapped batch index, a
+    transposed operand or a dropped term changes it), NumPy's int64 einsum, and batch = 1 against
+    the plain GEMM."""
+    A = np.array([[[1, 2], [3, 4], [-1, 0]], [[0, 1], [5, -6], [7, 7]]], dtype=np.int8)      # [2, 3, 2]
+    B = np.array([[[1, 0], [2, -1]], [[-3, 1], [1, 1]]], dtype=np.int8)                      # [2, 2, 2]
+    want = [[[1, 0], [3, 2], [-1, -2]], [[1, 1], [-21, -1], [-14, 14]]]
+    assert O.bmm_i32(A, B).tolist() == want
+    rng = np.random.default_rng(11)
+    A = rng.integers(-128, 128, (5, 17, 96), dtype=np.int8)
+    B = rng.integers(-128, 128, (5, 9, 96), dtype=np.int8)
+    ref = np.einsum("bik,bnk->bin", A.astype(np.int64), B.astype(np.int64))
+    got = O.bmm_i32(A, B)
+    np.testing.assert_array_equal(got, ref)
+    np.testing.assert_array_equal(O.bmm_i32(A[2:3], B[2:3])[0], O.gemm_i32(A[2], B[2]))
