@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one plain 1 GiB device copy (the reference kernel for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--no-bmm", action="store_true", help="skip the attention-shaped batched-product rows")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1")
@@ -202,6 +203,34 @@ def main():
     flatten_roofline = dict(bound="hbm", kernel="colabsmax + scale + flatten_quant", achieved=round(fqa["bytes"] / fqa["ms"] / 1e6, 1),
                             peak=HBM_PEAK_GBS, unit="GB/s", frac=round(fqa["bytes"] / fqa["ms"] / 1e6 / HBM_PEAK_GBS, 4))
 
+    # ---------------- batched integer product on attention shapes (reported beside the step) ----------------
+    # OPT-13B attention geometry (40 heads of 128) at 2048 tokens, 4 sequences: Q K^T [2048 x 2048 x 128] and
+    # P V [2048 x 128 x 2048] per head, 160 heads; per-tensor scales, bf16 output.  Both are bound by HBM:
+    # algorithmic bytes = operands read once + output written once.
+    bmm_rows = []
+    if not args.no_bmm:
+        heads, S, dh = 160, 2048, 128
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1234)
+        one = torch.ones(1, dtype=torch.float32, device=dev)
+        for name, Mb, Nb, Kb in (("QK^T", S, S, dh), ("PV", S, dh, S)):
+            for bits in (8, 4):
+                rb = Kb if bits == 8 else Kb // 2
+                Aq = torch.randint(-128, 128, (heads, Mb, rb), dtype=torch.int8, device=dev, generator=gen)
+                Bq = torch.randint(-128, 128, (heads, Nb, rb), dtype=torch.int8, device=dev, generator=gen)
+                if bits == 4:
+                    Aq, Bq = Aq.view(torch.uint8), Bq.view(torch.uint8)
+                Yb = torch.empty((heads, Mb, Nb), dtype=torch.bfloat16, device=dev)
+                f = fq.fq_bmm_i8 if bits == 8 else fq.fq_bmm_i4
+                t = event_time_ms(torch, lambda: f(Aq, Bq, one, one, Yb), args.steps)
+                nbytes = heads * ((Mb + Nb) * rb + Mb * Nb * 2)
+                row = dict(op=f"bmm_i{bits} {name}", batch=heads, M=Mb, N=Nb, K=Kb, ms=round(t, 4),
+                           gbs=round(nbytes / t / 1e6, 1), pct_hbm_peak=round(100 * nbytes / t / 1e6 / HBM_PEAK_GBS, 2),
+                           tops=round(2.0 * heads * Mb * Nb * Kb / t / 1e9, 1))
+                bmm_rows.append(row)
+                log("[kernel] " + json.dumps(row))
+                del Aq, Bq, Yb
+
     if args.copy_ref:
         src_buf = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst_buf = torch.empty_like(src_buf)
@@ -276,6 +305,7 @@ def main():
         "flatten_quant_roofline": flatten_roofline,
         "cpu_baseline": cpu,
         "layers": rows,
+        "bmm": bmm_rows,
     }
     print(json.dumps(out), flush=True)
 

@@ -182,6 +182,29 @@ int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad,
                const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * fq_bmm_i8 / fq_bmm_i4 — the batched form of the integer GEMM (Sec. 5.1: the quantized BMM function
+ * that stands beside the quantized linear layer, for attention's two products).  The paper gives
+ * no detail beyond INT8 / INT4 operands; the reading taken: per-tensor scales over the whole batched
+ * tensors, no flattening of these operands.
+ *
+ *   acc[b,i,n] = sum_{p < Kpad} Aq[b,i,p] * Bq[b,n,p],   b < batch            (exact, int32)
+ *   Y[b,i,n]   = the epilogue of fq_gemm_i8 with *s_a, *s_b.
+ *
+ * Aq  batch matrices [M, Kpad] int8 (fq_bmm_i4: [M, Kpad/2] packed), rows dense, matrix b at byte
+ *     offset b * stride_a; Bq likewise [N, Kpad] with stride_b.  Strides are in bytes, multiples of
+ *     16, at least one matrix.  Both operands have the reduction index last: for P V pass V^T.
+ * Y   matrix b at element offset b * stride_y, row stride ldy >= N elements.
+ * batch in [1, 65535]; other limits as fq_gemm_i8.  To quantize an operand per tensor, call
+ * fq_flatten_quant_act on its [batch * rows, K] view with an identity map (T above every channel maximum).
+ * ------------------------------------------------------------------------------------------- */
+int fq_bmm_i8(const int8_t* Aq, const int8_t* Bq, int batch, int M, int N, int Kpad,
+              long long stride_a, long long stride_b, const float* s_a, const float* s_b,
+              void* Y, int y_dtype, int ldy, long long stride_y, void* stream);
+int fq_bmm_i4(const uint8_t* Aq, const uint8_t* Bq, int batch, int M, int N, int Kpad,
+              long long stride_a, long long stride_b, const float* s_a, const float* s_b,
+              void* Y, int y_dtype, int ldy, long long stride_y, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * fq_linear — the end-to-end inference call: fq_flatten_quant_act followed by fq_gemm_i8 /
  * fq_gemm_i4 on one stream.  Wq / s_w come from fq_flatten_weights with the same map and bits.
  * workspace  fq_linear_workspace_bytes(M, K, Kpad, bits) bytes, device, 16-byte aligned; holds

@@ -22,7 +22,7 @@ ERR_NAMES = {1: "FQ_ERR_NULL", 2: "FQ_ERR_SHAPE", 3: "FQ_ERR_DTYPE", 4: "FQ_ERR_
 SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_weights",
            "fq_weights_workspace_bytes", "fq_flatten_quant_act", "fq_act_workspace_bytes", "fq_gemm_i8",
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
-           "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax"]
+           "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4"]
 
 
 class FqError(RuntimeError):
@@ -62,6 +62,9 @@ def lib() -> ctypes.CDLL:
     L.fq_act_workspace_bytes.argtypes = [c_int, c_int]
     for f in (L.fq_gemm_i8, L.fq_gemm_i4):
         f.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, c_int, c_int, vp]
+    for f in (L.fq_bmm_i8, L.fq_bmm_i4):
+        f.argtypes = [vp, vp, c_int, c_int, c_int, c_int, ctypes.c_longlong, ctypes.c_longlong, vp, vp, vp, c_int,
+                      c_int, ctypes.c_longlong, vp]
     L.fq_linear.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, c_int, c_int, vp, vp, c_int,
                             c_int, vp, c_size_t, vp]
     L.fq_linear_workspace_bytes.restype = c_size_t
@@ -208,6 +211,30 @@ def fq_gemm_i4(Xq, Wq, s_x, s_w, Y, stream=None) -> None:
     M, half = Xq.shape
     N = Wq.shape[0]
     _gemm(lib().fq_gemm_i4, Xq, Wq, M, N, 2 * half, s_x, s_w, Y, stream)
+
+
+def _bmm(fn, Aq, Bq, Kpad, s_a, s_b, Y, stream):
+    for t, name in ((Aq, "Aq"), (Bq, "Bq"), (Y, "Y")):
+        if not t.is_cuda or t.dim() != 3 or t.stride(2) != 1:
+            raise ValueError(f"{name} must be a 3-D device tensor with a contiguous last dimension")
+    batch, M, rowbytes = Aq.shape
+    N = Bq.shape[1]
+    if Bq.shape[0] != batch or Bq.shape[2] != rowbytes or Y.shape != (batch, M, N):
+        raise ValueError("shape mismatch between Aq, Bq and Y")
+    if Aq.stride(1) != rowbytes or Bq.stride(1) != rowbytes:
+        raise ValueError("operand rows must be dense")
+    _check(fn(Aq.data_ptr(), Bq.data_ptr(), batch, M, N, Kpad, Aq.stride(0), Bq.stride(0), _ptr(s_a), _ptr(s_b),
+              Y.data_ptr(), _dtype_code(Y), Y.stride(1), Y.stride(0), _stream(stream)))
+
+
+def fq_bmm_i8(Aq, Bq, s_a, s_b, Y, stream=None) -> None:
+    """Aq int8 [batch, M, Kpad], Bq int8 [batch, N, Kpad] -> Y [batch, M, N]."""
+    _bmm(lib().fq_bmm_i8, Aq, Bq, Aq.shape[2], s_a, s_b, Y, stream)
+
+
+def fq_bmm_i4(Aq, Bq, s_a, s_b, Y, stream=None) -> None:
+    """Aq uint8 [batch, M, Kpad/2], Bq uint8 [batch, N, Kpad/2] (packed nibbles) -> Y [batch, M, N]."""
+    _bmm(lib().fq_bmm_i4, Aq, Bq, 2 * Aq.shape[2], s_a, s_b, Y, stream)
 
 
 def fq_linear(X, src_idx, rep, Wq, s_w, bits: int, Y, workspace, absmax_in=None, stream=None) -> None:

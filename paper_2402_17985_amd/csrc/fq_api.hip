@@ -263,6 +263,39 @@ int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, con
     return launch_gemm_int(Xq, Wq, M, N, Kpad, 4, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+int bmm_common(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, long long stride_a,
+               long long stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy, long long stride_y,
+               void* stream)
+{
+    clear_error();
+    if (int rc = check_gemm(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy)) return rc;
+    if (batch < 1 || batch > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", batch);
+    const long long rowbytes = bits == 8 ? Kpad : Kpad / 2;
+    if (stride_a < (long long)M * rowbytes || stride_b < (long long)N * rowbytes)
+        return fail(FQ_ERR_SHAPE, "operand batch stride smaller than one matrix (%lld, %lld bytes)", stride_a, stride_b);
+    if (stride_a % 16 != 0 || stride_b % 16 != 0)
+        return fail(FQ_ERR_ALIGN, "operand batch strides must be multiples of 16 bytes");
+    if (stride_y < (long long)(M - 1) * ldy + N) return fail(FQ_ERR_SHAPE, "output batch stride %lld too small", stride_y);
+    return launch_bmm_int(Aq, Bq, batch, M, N, Kpad, bits, (size_t)stride_a, (size_t)stride_b, s_a, s_b, Y, y_dtype, ldy,
+                          (size_t)stride_y * elem_size(y_dtype), static_cast<hipStream_t>(stream));
+}
+}  // namespace
+
+int fq_bmm_i8(const int8_t* Aq, const int8_t* Bq, int batch, int M, int N, int Kpad, long long stride_a,
+              long long stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy, long long stride_y,
+              void* stream)
+{
+    return bmm_common(Aq, Bq, batch, M, N, Kpad, 8, stride_a, stride_b, s_a, s_b, Y, y_dtype, ldy, stride_y, stream);
+}
+
+int fq_bmm_i4(const uint8_t* Aq, const uint8_t* Bq, int batch, int M, int N, int Kpad, long long stride_a,
+              long long stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy, long long stride_y,
+              void* stream)
+{
+    return bmm_common(Aq, Bq, batch, M, N, Kpad, 4, stride_a, stride_b, s_a, s_b, Y, y_dtype, ldy, stride_y, stream);
+}
+
 int fq_linear(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx, const int32_t* rep,
               int Kpad, const void* Wq, const float* s_w, int N, int bits, const float* absmax_in, void* Y,
               int y_dtype, int ldy, void* workspace, size_t workspace_bytes, void* stream)

@@ -69,6 +69,13 @@ __device__ __forceinline__ void dma16_addr(const uint8_t* lane_address, uint32_t
 // 16 zero bytes in device memory: the source of DMA lanes that fall beyond the end of a row.
 __device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
 
+// Batched launches: `count` independent problems, operand and output base addresses advancing by these
+// byte strides (count = 1, strides 0 for a single GEMM).
+struct Batch {
+    int count;
+    size_t stride_a, stride_b, stride_y;
+};
+
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
 
@@ -590,9 +597,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
                                                                 int rowbytes, const float* __restrict__ s_x,
                                                                 const float* __restrict__ s_w,
                                                                 void* __restrict__ Y, int y_dtype, int ldy,
-                                                                int tiles_m, int tiles_n, int n_main)
+                                                                int tiles_m, int tiles_n, int n_main, Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    // batched launches: blockIdx.y selects the problem
+    A += (size_t)blockIdx.y * bt.stride_a;
+    B += (size_t)blockIdx.y * bt.stride_b;
+    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
     const int wg = blockIdx.x;
     int tile_m, tile_n;
     if (wg < n_main) {
@@ -619,8 +630,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
                                                                 int rowbytes, const float* __restrict__ s_x,
                                                                 const float* __restrict__ s_w,
                                                                 void* __restrict__ Y, int y_dtype, int ldy,
-                                                                int tiles_m, int tiles_n)
+                                                                int tiles_m, int tiles_n, Batch bt)
 {
+    A += (size_t)blockIdx.y * bt.stride_a;
+    B += (size_t)blockIdx.y * bt.stride_b;
+    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BKB / 16;          // chunks per row per stage
     constexpr int RPP = NT / CPR;          // rows covered by one pass of the loader
@@ -746,7 +760,7 @@ int compute_units()
 
 template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
 int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
-               void* Y, int y_dtype, int ldy, hipStream_t stream)
+               void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
     // the DMA kernel addresses rows with 32-bit byte offsets
     if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
@@ -763,13 +777,13 @@ int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const f
     const int cus = compute_units();
     const int r = (int)(tiles % cus);
     int n_main = (int)tiles, n_tail = 0;
-    if (HALF_OK && r > 0 && 2 * r <= cus) {
+    if (HALF_OK && bt.count == 1 && r > 0 && 2 * r <= cus) {
         n_tail = r;
         n_main = (int)tiles - r;
     }
-    kern<<<dim3((unsigned)(n_main + 2 * n_tail)), dim3(WM * WN * 64), smem, stream>>>(
+    kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(WM * WN * 64), smem, stream>>>(
         static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
-        tiles_m, tiles_n, n_main);
+        tiles_m, tiles_n, n_main, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
@@ -777,7 +791,7 @@ int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const f
 
 template <int MODE, int BM, int BN, int BKB, int WM, int WN>
 int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
-               void* Y, int y_dtype, int ldy, hipStream_t stream)
+               void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
     auto kern = gemm_reg_kernel<MODE, BM, BN, BKB, WM, WN>;
     constexpr int smem = 2 * (BM + BN) * BKB;
@@ -786,9 +800,9 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const long long tiles = (long long)tiles_m * tiles_n;
     if (tiles > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
-    kern<<<dim3((unsigned)tiles), dim3(WM * WN * 64), smem, stream>>>(static_cast<const uint8_t*>(A),
-                                                                      static_cast<const uint8_t*>(B), M, N, rowbytes,
-                                                                      s_x, s_w, Y, y_dtype, ldy, tiles_m, tiles_n);
+    kern<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(WM * WN * 64), smem, stream>>>(
+        static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+        tiles_m, tiles_n, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
@@ -798,24 +812,27 @@ constexpr int NUM_VARIANTS = 10;
 
 template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
-             void* Y, int y_dtype, int ldy, hipStream_t stream)
+             void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
+    if (bt.count < 1 || bt.count > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", bt.count);
     int v = g_variant;
     if (v < 0) {
-        const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-        v = (big_tiles >= 192) ? 7 : 6;
+        const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
+        // short reductions (a few k-tiles) leave the output write as the bound: the smaller tile runs
+        // two workgroups per CU so that one's epilogue overlaps the other's loads
+        v = (big_tiles >= 192 && rowbytes > 512 && N > 128) ? 7 : 6;
     }
     switch (v) {
-    case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 1: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 0>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 2: return launch_reg<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 3: return launch_dma<MODE, 256, 256, 64, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
-    case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, stream);
+    case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 1: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 0>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 2: return launch_reg<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 3: return launch_dma<MODE, 256, 256, 64, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }
@@ -832,13 +849,24 @@ int set_gemm_variant(int v)
 int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits, const float* s_x,
                     const float* s_w, void* Y, int y_dtype, int ldy, hipStream_t stream)
 {
-    if (bits == 8) return dispatch<MODE_I8>(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, stream);
-    return dispatch<MODE_I4>(Xq, Wq, M, N, Kpad / 2, s_x, s_w, Y, y_dtype, ldy, stream);
+    const Batch one = {1, 0, 0, 0};
+    if (bits == 8) return dispatch<MODE_I8>(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, one, stream);
+    return dispatch<MODE_I4>(Xq, Wq, M, N, Kpad / 2, s_x, s_w, Y, y_dtype, ldy, one, stream);
+}
+
+int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, size_t stride_a,
+                   size_t stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy,
+                   size_t stride_y_bytes, hipStream_t stream)
+{
+    const Batch bt = {batch, stride_a, stride_b, stride_y_bytes};
+    if (bits == 8) return dispatch<MODE_I8>(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy, bt, stream);
+    return dispatch<MODE_I4>(Aq, Bq, M, N, Kpad / 2, s_a, s_b, Y, y_dtype, ldy, bt, stream);
 }
 
 int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, hipStream_t stream)
 {
-    return dispatch<MODE_BF16>(X, W, M, N, K * 2, nullptr, nullptr, Y, FQ_BF16, ldy, stream);
+    const Batch one = {1, 0, 0, 0};
+    return dispatch<MODE_BF16>(X, W, M, N, K * 2, nullptr, nullptr, Y, FQ_BF16, ldy, one, stream);
 }
 
 }  // namespace fq

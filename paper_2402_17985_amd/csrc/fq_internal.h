@@ -49,6 +49,11 @@ int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int 
                     const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
                     hipStream_t stream);
 
+// `batch` independent products; operand strides in bytes, stride_y_bytes in bytes
+int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, size_t stride_a,
+                   size_t stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy,
+                   size_t stride_y_bytes, hipStream_t stream);
+
 int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy,
                      hipStream_t stream);
 

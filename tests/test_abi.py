@@ -109,6 +109,17 @@ def test_device_calls_validate_before_launching():
     assert L.fq_flatten_quant_act(*args(wsb=ws - 1)) == 7
     assert b"workspace" in L.fq_last_error_string()
     assert L.fq_gemm_bf16(dummy, dummy, 4, 4, 12, dummy, 4, None) == 2
+    # batched product: batch count, operand strides (size, 16-byte multiple), output stride
+    bmm = lambda batch=2, sa=128, sb=128, sy=16, f=L.fq_bmm_i8: f(dummy, dummy, batch, 4, 4, 32, sa, sb, dummy, dummy,
+                                                                  dummy, fq.FQ_F32, 4, sy, None)
+    assert bmm(batch=0) == 4
+    assert bmm(batch=70000) == 4
+    assert bmm(sa=64) == 2
+    assert bmm(sb=136) == 5
+    assert bmm(sy=15) == 2
+    assert bmm(sa=32, f=L.fq_bmm_i4) == 2                    # a packed 4 x 32 matrix is 64 bytes
+    assert L.fq_channel_absmax(dummy, fq.FQ_BF16, 4, 64, 60, 0, dummy, None) == 2
+    assert L.fq_channel_absmax(dummy, fq.FQ_BF16, 4, 64, 64, 0, None, None) == 1
     assert L.fq_gemm_select(1700) == 4
     assert L.fq_gemm_select(-1) == 0
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 8) >= 8 * 64 + ws

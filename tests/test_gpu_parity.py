@@ -301,3 +301,68 @@ def test_channel_absmax_and_boxplot_threshold(cfg, over):
     assert (kp, kpad) == (kp_o, kpad_o)
     np.testing.assert_array_equal(src, src_o)
     np.testing.assert_array_equal(rep, rep_o)
+
+
+# ------------------------------------------------------------------------------------------
+# batched integer product (attention-shaped)
+# ------------------------------------------------------------------------------------------
+def _bmm_operands(seed, batch, M, N, Kpad, bits):
+    rng = np.random.default_rng([seed, batch, M, N, Kpad, bits])
+    lo, hi = (-128, 128) if bits == 8 else (-8, 8)
+    A = rng.integers(lo, hi, (batch, M, Kpad), dtype=np.int8)
+    B = rng.integers(lo, hi, (batch, N, Kpad), dtype=np.int8)
+    return A, B
+
+
+def _to_dev_q(q, bits):
+    if bits == 8:
+        return torch.from_numpy(q).to(DEV)
+    b, r, k = q.shape
+    return torch.from_numpy(O.pack_i4(q.reshape(b * r, k)).reshape(b, r, k // 2)).to(DEV)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("batch,M,N,Kpad", [
+    (3, 200, 200, 128),        # Q K^T shape: short reduction, ragged tiles
+    (5, 257, 128, 320),        # P V shape: N = head size, reduction over the sequence
+    (2, 64, 40, 32),           # tiny
+    (1, 130, 300, 1024),       # batch of one equals the plain GEMM
+    (7, 129, 131, 96),
+])
+def test_bmm_accumulators_bit_exact(batch, M, N, Kpad, bits):
+    A, B = _bmm_operands(1, batch, M, N, Kpad, bits)
+    ref = O.bmm_i32(A, B)
+    Ad, Bd = _to_dev_q(A, bits), _to_dev_q(B, bits)
+    Y = torch.full((batch, M, N), -7, dtype=torch.int32, device=DEV)
+    (fq.fq_bmm_i8 if bits == 8 else fq.fq_bmm_i4)(Ad, Bd, None, None, Y)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(Y.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("variant", [0, 2, 5, 6, 7])
+def test_bmm_variants_and_padded_strides(variant):
+    """Every kernel family with batch strides larger than one matrix (operands and output live in
+    wider buffers; the gaps must stay untouched) and a 2-byte dequantized output."""
+    batch, M, N, Kpad = 4, 300, 260, 256
+    A, B = _bmm_operands(2, batch, M, N, Kpad, 8)
+    ref = O.bmm_i32(A, B)
+    Abuf = torch.zeros((batch, M + 5, Kpad), dtype=torch.int8, device=DEV)
+    Bbuf = torch.zeros((batch, N + 3, Kpad), dtype=torch.int8, device=DEV)
+    Abuf[:, :M] = torch.from_numpy(A).to(DEV)
+    Bbuf[:, :N] = torch.from_numpy(B).to(DEV)
+    s_a, s_b = scalar(0.013), scalar(0.0021)
+    Ybuf = torch.full((batch, M + 2, N + 8), 99.0, dtype=torch.bfloat16, device=DEV)
+    Yi = torch.zeros((batch, M, N), dtype=torch.int32, device=DEV)
+    fq.fq_gemm_select(variant)
+    try:
+        fq.fq_bmm_i8(Abuf[:, :M], Bbuf[:, :N], s_a, s_b, Ybuf[:, :M, :N])
+        fq.fq_bmm_i8(Abuf[:, :M], Bbuf[:, :N], None, None, Yi)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_gemm_select(-1)
+    np.testing.assert_array_equal(Yi.cpu().numpy(), ref)
+    y_ref = O.dequant(ref, np.float32(0.013), np.float32(0.0021))
+    got = bf16_to_f64(Ybuf[:, :M, :N])
+    assert rel_err(got, y_ref).max() <= 2.0 ** -8
+    full = Ybuf.float().cpu().numpy()
+    assert (full[:, M:, :] == 99.0).all() and (full[:, :, N:] == 99.0).all()
