@@ -523,3 +523,136 @@ int fqo_bmm_i32(const int8_t *Aq, const int8_t *Bq, int batch, int M, int N, int
             }
     return bad ? FQO_ERR_OVERFLOW : FQO_OK;
 }
+
+/* ==========================================================================================
+ * The printed split of Eq. 3 ("peel") and flattening of the weights' own large channels
+ * (Sec. 4.1, last paragraph).
+ * ======================================================================================== */
+
+/* ------------------------------------------------------------------------------------------
+ * Two-sided plan.  Channel j is flattened on the activation side into nx_j = max(1,
+ * ceil(max|X_j| / T_x)) shares (Eq. 2, reading as in fqo_plan) and, when chmax_w is given, on
+ * the weight side into nw_j = max(1, ceil(max|W_j| / T_w)) shares (Sec. 4.1: the same
+ * construction applied to the weights, the activation channel being the repeated one).  With
+ * equal shares x/nx and w/nw the product x*w is recovered as the sum over nx*nw slots, so
+ * channel j occupies c_j = nx_j * nw_j slots: index j and c_j - 1 appended slots, channels in
+ * increasing j (Eq. 3's index rule).  Per slot: src, rep_x = nx, rep_w = nw, ord = the slot's
+ * ordinal among its channel's slots (0 = the original position).  Padding: -1, 0, 0, 0.
+ * chmax_w == NULL means no weight-side flattening (nw = 1); then src / rep_x equal fqo_plan's.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_plan_xw(const float *chmax_x, float T_x, const float *chmax_w, float T_w, int K, int align,
+                int32_t *src, int32_t *rep_x, int32_t *rep_w, int32_t *ord, int cap,
+                int *Kprime_out, int *Kpad_out)
+{
+    if (!chmax_x || K <= 0 || align <= 0 || !(T_x > 0.0f) || isinf(T_x)) return FQO_ERR_ARG;
+    if (chmax_w && (!(T_w > 0.0f) || isinf(T_w))) return FQO_ERR_ARG;
+    long long total = 0;
+    for (int j = 0; j < K; ++j) {
+        if (!(chmax_x[j] >= 0.0f) || isinf(chmax_x[j])) return FQO_ERR_ARG;
+        long long nx = (long long)ceil((double)chmax_x[j] / (double)T_x), nw = 1;
+        if (nx < 1) nx = 1;
+        if (chmax_w) {
+            if (!(chmax_w[j] >= 0.0f) || isinf(chmax_w[j])) return FQO_ERR_ARG;
+            nw = (long long)ceil((double)chmax_w[j] / (double)T_w);
+            if (nw < 1) nw = 1;
+        }
+        if (nx > 0x3fffffff || nw > 0x3fffffff) return FQO_ERR_OVERFLOW;
+        total += nx * nw;
+        if (total > 0x3fffffff) return FQO_ERR_OVERFLOW;
+    }
+    long long Kpad = (total + align - 1) / align * align;
+    if (Kprime_out) *Kprime_out = (int)total;
+    if (Kpad_out) *Kpad_out = (int)Kpad;
+    if (cap == 0) return FQO_OK;
+    if (!src || !rep_x) return FQO_ERR_ARG;
+    if (cap < Kpad) return FQO_ERR_CAP;
+    int next = K;
+    for (int j = 0; j < K; ++j) {
+        int nx = (int)ceil((double)chmax_x[j] / (double)T_x), nw = 1;
+        if (nx < 1) nx = 1;
+        if (chmax_w) {
+            nw = (int)ceil((double)chmax_w[j] / (double)T_w);
+            if (nw < 1) nw = 1;
+        }
+        for (int e = 0; e < nx * nw; ++e) {
+            int p = (e == 0) ? j : next++;
+            src[p] = j;
+            rep_x[p] = nx;
+            if (rep_w) rep_w[p] = nw;
+            if (ord) ord[p] = e;
+        }
+    }
+    for (int p = next; p < (int)Kpad; ++p) {
+        src[p] = -1;
+        rep_x[p] = 0;
+        if (rep_w) rep_w[p] = 0;
+        if (ord) ord[p] = 0;
+    }
+    return FQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Weights with their own channels flattened (Sec. 4.1, last paragraph; Eq. 1): slot p of row n
+ * holds W[n, src[p]] / rep_w[p]; per-tensor absmax of that tensor
+ *   a_w = max_p fl32( max_n |W[n, src[p]]| / (float)rep_w[p] ),
+ * s_w = fl32(a_w / qmax), multiplier m_p = fl32(qmax / (rep_w[p] * a_w)) (float64 quotient), one
+ * fp32 multiply, round-half-even, clamp.  The same arithmetic as the activation's equal split,
+ * applied to the N x K weight array.
+ * ---------------------------------------------------------------------------------------- */
+int fqo_flatten_weights_split(const float *W, int N, int K, const int32_t *src, const int32_t *rep_w,
+                              int Kpad, int bits, int8_t *Wq_out, float *s_w_out)
+{
+    if (!W || !src || !rep_w || !Wq_out || !s_w_out || N <= 0 || K <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    float a_w = fqo_act_absmax_dynamic(W, N, K, K, src, rep_w, Kpad);
+    return fqo_flatten_quant_act(W, N, K, K, src, rep_w, Kpad, bits, a_w, Wq_out, s_w_out);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Eq. 3 as printed, quantized (Eq. 1).  The slot with ordinal e of channel j (e = 0 the
+ * original position) holds  v = sign(x) * min(max(|x| - e*T, 0), T):  floor(|x|/T) slots of T,
+ * then the remainder, then zeros (the paper prints the positive case; negative values are
+ * treated through |x|).  All in fp32, in this order:
+ *   t = fl32((float)e * T);  mag = fl32(|x| - t) clamped to [0, T];  v = +-mag;
+ *   q = clamp(rne(fl32(v * m)), qmin, qmax),  m = fl32(qmax / a')  (float64 quotient).
+ * a' is the absmax of the flattened tensor: at most T by construction; the caller passes T
+ * (static, the paper's setting) or fqo_act_absmax_peel's value.  s_x = fl32(a' / qmax);
+ * a' = 0 gives zeros and s_x = 1.  Weights are plainly repeated (Eq. 4) for this split.
+ * ---------------------------------------------------------------------------------------- */
+float fqo_act_absmax_peel(const float *X, int M, int K, int ldx, float T)
+{
+    float a = 0.0f;
+    for (int i = 0; i < M; ++i)
+        for (int j = 0; j < K; ++j) {
+            float t = fabsf(X[(size_t)i * ldx + j]);
+            if (t > a) a = t;
+        }
+    return a > T ? T : a;
+}
+
+int fqo_flatten_quant_act_peel(const float *X, int M, int K, int ldx, const int32_t *src,
+                               const int32_t *ord, int Kpad, int bits, float T, float a_prime,
+                               int8_t *Xq_out, float *s_x_out)
+{
+    if (!X || !src || !ord || !Xq_out || !s_x_out || M <= 0 || K <= 0 || Kpad <= 0) return FQO_ERR_ARG;
+    if (bits != 8 && bits != 4) return FQO_ERR_ARG;
+    if (!(T > 0.0f) || isinf(T) || !(a_prime >= 0.0f) || isinf(a_prime)) return FQO_ERR_ARG;
+    int qmax = qmax_of(bits);
+    *s_x_out = (a_prime == 0.0f) ? 1.0f : (float)((double)a_prime / (double)qmax);
+    float m = (a_prime == 0.0f) ? 0.0f : (float)((double)qmax / (double)a_prime);
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i)
+        for (int p = 0; p < Kpad; ++p) {
+            int j = src[p], q = 0;
+            if (j >= 0) {
+                float x = X[(size_t)i * ldx + j];
+                float t = (float)ord[p] * T;
+                float mag = fabsf(x) - t;
+                if (mag < 0.0f) mag = 0.0f;
+                if (mag > T) mag = T;
+                float v = (x < 0.0f) ? -mag : mag;
+                q = round_clamp(v * m, bits);
+            }
+            Xq_out[(size_t)i * Kpad + p] = (int8_t)q;
+        }
+    return FQO_OK;
+}

@@ -23,6 +23,7 @@ def lib():
         _lib.fqo_absmax.restype = ctypes.c_float
         _lib.fqo_act_absmax_dynamic.restype = ctypes.c_float
         _lib.fqo_dot_i32.restype = ctypes.c_int32
+        _lib.fqo_act_absmax_peel.restype = ctypes.c_float
     return _lib
 
 
@@ -275,3 +276,56 @@ def bmm_i32(Aq, Bq):
     rc = lib().fqo_bmm_i32(_p(Aq, ctypes.c_int8), _p(Bq, ctypes.c_int8), batch, M, N, Kpad, _p(out, ctypes.c_int32))
     _check(rc, "fqo_bmm_i32")
     return out
+
+
+def plan_xw(chmax_x, T_x, chmax_w=None, T_w=1.0, align=32):
+    """Two-sided plan.  Returns (src, rep_x, rep_w, ord, Kprime, Kpad)."""
+    chmax_x = _f32(chmax_x)
+    K = chmax_x.shape[0]
+    cw = None if chmax_w is None else _f32(chmax_w)
+    pw = None if cw is None else _p(cw, ctypes.c_float)
+    kp, kpad = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().fqo_plan_xw(_p(chmax_x, ctypes.c_float), ctypes.c_float(T_x), pw, ctypes.c_float(T_w), K, align,
+                           None, None, None, None, 0, ctypes.byref(kp), ctypes.byref(kpad))
+    _check(rc, "fqo_plan_xw(size query)")
+    arrs = [np.empty(kpad.value, dtype=np.int32) for _ in range(4)]
+    rc = lib().fqo_plan_xw(_p(chmax_x, ctypes.c_float), ctypes.c_float(T_x), pw, ctypes.c_float(T_w), K, align,
+                           *[_p(a, ctypes.c_int32) for a in arrs], kpad.value, ctypes.byref(kp), ctypes.byref(kpad))
+    _check(rc, "fqo_plan_xw")
+    return arrs[0], arrs[1], arrs[2], arrs[3], kp.value, kpad.value
+
+
+def flatten_weights_split(W, src, rep_w, bits):
+    """Weights with their own channels split (equal shares).  Returns (Wq int8 [N, Kpad], s_w)."""
+    W = _f32(W)
+    N, K = W.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    rep_w = np.ascontiguousarray(rep_w, dtype=np.int32)
+    out = np.empty((N, src.shape[0]), dtype=np.int8)
+    s_w = ctypes.c_float(0)
+    rc = lib().fqo_flatten_weights_split(_p(W, ctypes.c_float), N, K, _p(src, ctypes.c_int32),
+                                         _p(rep_w, ctypes.c_int32), src.shape[0], bits, _p(out, ctypes.c_int8),
+                                         ctypes.byref(s_w))
+    _check(rc, "fqo_flatten_weights_split")
+    return out, np.float32(s_w.value)
+
+
+def act_absmax_peel(X, T) -> np.float32:
+    X = _f32(X)
+    M, K = X.shape
+    return np.float32(lib().fqo_act_absmax_peel(_p(X, ctypes.c_float), M, K, K, ctypes.c_float(T)))
+
+
+def flatten_quant_act_peel(X, src, ord_, bits, T, a_prime):
+    """Eq. 3 as printed + Eq. 1.  Returns (Xq int8 [M, Kpad], s_x)."""
+    X = _f32(X)
+    M, K = X.shape
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    ord_ = np.ascontiguousarray(ord_, dtype=np.int32)
+    out = np.empty((M, src.shape[0]), dtype=np.int8)
+    s_x = ctypes.c_float(0)
+    rc = lib().fqo_flatten_quant_act_peel(_p(X, ctypes.c_float), M, K, K, _p(src, ctypes.c_int32),
+                                          _p(ord_, ctypes.c_int32), src.shape[0], bits, ctypes.c_float(T),
+                                          ctypes.c_float(a_prime), _p(out, ctypes.c_int8), ctypes.byref(s_x))
+    _check(rc, "fqo_flatten_quant_act_peel")
+    return out, np.float32(s_x.value)
