@@ -163,6 +163,43 @@ int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx,
 size_t fq_act_workspace_bytes(int K, int Kpad);
 
 /* ---------------------------------------------------------------------------------------------
+ * Eq. 3 as printed ("peel" split) and flattening of the weights' own channels (Sec. 4.1, last
+ * paragraph).  The map layout, the GEMM and its epilogue are the ones above.
+ *
+ * fq_flatten_plan_xw — HOST.  Channel j is split into nx_j = max(1, ceil(chmax_x[j] / T_x)) shares on
+ *   the activation side and, when chmax_w_host != NULL (chmax_w[j] = max_n |W[n, j]|), into
+ *   nw_j = max(1, ceil(chmax_w[j] / T_w)) shares on the weight side; x*w is then the sum over
+ *   nx_j * nw_j slots of (x / nx_j)(w / nw_j), so channel j occupies that many slots: index j plus
+ *   appended slots, channels in increasing j (Eq. 3's index rule).  Per slot: src_idx, rep_x = nx,
+ *   rep_w = nw (may be NULL), ord = the slot's ordinal within its channel, 0 at the original position
+ *   (may be NULL).  Padding: -1, 0, 0, 0.  With chmax_w_host == NULL, src_idx / rep_x equal
+ *   fq_flatten_plan's.  cap = 0 queries the sizes, as in fq_flatten_plan.
+ *
+ * fq_flatten_weights_split — weights with their own large channels split into equal shares:
+ *   slot p of row n holds W[n, src_idx[p]] / rep_w[p], quantized per tensor with
+ *   a_w = max_p fl32(max_n |W[n, src_idx[p]]| / rep_w[p]) exactly as fq_flatten_quant_act does for the
+ *   activation (dynamic).  Pair it with fq_flatten_quant_act(X, src_idx, rep_x).
+ *
+ * fq_flatten_quant_act_peel — the split Eq. 3 prints: the slot with ordinal e of channel j holds
+ *   v = sign(x) * min(max(|x| - fl32(e * T), 0), T)  (floor(|x| / T) slots of T, the remainder, zeros;
+ *   negative values through |x|), then Eq. 1 with a single multiplier:
+ *   Xq = clamp(rne(fl32(v * m)), qmin, qmax), m = fl32(qmax / a'), s_x = fl32(a' / qmax);
+ *   a' = *absmax_in when given (the paper's static setting: a' = T), else min(T, max |X|).
+ *   The weights are plainly repeated (fq_flatten_weights) for this split; ord comes from
+ *   fq_flatten_plan_xw with chmax_w_host = NULL.  Buffers, workspace and limits as fq_flatten_quant_act.
+ * ------------------------------------------------------------------------------------------- */
+int fq_flatten_plan_xw(const float* chmax_x_host, float T_x, const float* chmax_w_host, float T_w, int K, int align,
+                       int32_t* src_idx_host, int32_t* rep_x_host, int32_t* rep_w_host, int32_t* ord_host,
+                       int cap, int* Kprime_out, int* Kpad_out);
+int fq_flatten_weights_split(const void* W, int w_dtype, int N, int K, int ldw,
+                             const int32_t* src_idx, const int32_t* rep_w, int Kpad, int bits,
+                             void* Wq_out, float* s_w_out, void* workspace, size_t workspace_bytes, void* stream);
+int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx,
+                              const int32_t* src_idx, const int32_t* ord, int Kpad, int bits, float T,
+                              const float* absmax_in, void* Xq_out, float* s_x_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * fq_gemm_i8 / fq_gemm_i4 — integer GEMM with int32 accumulation and the fused per-tensor
  * dequantize epilogue (Sec. 5.1; the inverse of Eq. 1 applied to the product).
  *

@@ -22,7 +22,8 @@ ERR_NAMES = {1: "FQ_ERR_NULL", 2: "FQ_ERR_SHAPE", 3: "FQ_ERR_DTYPE", 4: "FQ_ERR_
 SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_weights",
            "fq_weights_workspace_bytes", "fq_flatten_quant_act", "fq_act_workspace_bytes", "fq_gemm_i8",
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
-           "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4"]
+           "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
+           "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel"]
 
 
 class FqError(RuntimeError):
@@ -52,6 +53,11 @@ def lib() -> ctypes.CDLL:
                                   ctypes.POINTER(c_int)]
     L.fq_threshold_boxplot.argtypes = [vp, c_int, c_float, ctypes.POINTER(c_float)]
     L.fq_smooth_scales.argtypes = [vp, vp, c_int, c_float, vp]
+    L.fq_flatten_plan_xw.argtypes = [vp, c_float, vp, c_float, c_int, c_int, vp, vp, vp, vp, c_int,
+                                     ctypes.POINTER(c_int), ctypes.POINTER(c_int)]
+    L.fq_flatten_weights_split.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, vp, vp, vp, c_size_t, vp]
+    L.fq_flatten_quant_act_peel.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, c_float, vp, vp, vp,
+                                            vp, c_size_t, vp]
     L.fq_channel_absmax.argtypes = [vp, c_int, c_int, c_int, c_int, c_int, vp, vp]
     L.fq_flatten_weights.argtypes = [vp, c_int, c_int, c_int, c_int, vp, c_int, c_int, vp, vp, vp, c_size_t, vp]
     L.fq_weights_workspace_bytes.restype = c_size_t
@@ -133,6 +139,24 @@ def fq_flatten_plan(chmax: np.ndarray, T: float, align: int = 32) -> Tuple[np.nd
     return src, rep, kp.value, kpad.value
 
 
+def fq_flatten_plan_xw(chmax_x: np.ndarray, T_x: float, chmax_w: Optional[np.ndarray] = None, T_w: float = 1.0,
+                       align: int = 32):
+    """Host call.  Returns (src_idx, rep_x, rep_w, ord, Kprime, Kpad), int32 arrays of Kpad entries."""
+    chmax_x = np.ascontiguousarray(chmax_x, dtype=np.float32)
+    K = chmax_x.shape[0]
+    cw = None if chmax_w is None else np.ascontiguousarray(chmax_w, dtype=np.float32)
+    if cw is not None and cw.shape != chmax_x.shape:
+        raise ValueError("chmax_x and chmax_w must have the same length")
+    pw = None if cw is None else cw.ctypes.data
+    kp, kpad = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().fq_flatten_plan_xw(chmax_x.ctypes.data, T_x, pw, T_w, K, align, None, None, None, None, 0,
+                                    ctypes.byref(kp), ctypes.byref(kpad)))
+    arrs = [np.empty(kpad.value, dtype=np.int32) for _ in range(4)]
+    _check(lib().fq_flatten_plan_xw(chmax_x.ctypes.data, T_x, pw, T_w, K, align, *[a.ctypes.data for a in arrs],
+                                    kpad.value, ctypes.byref(kp), ctypes.byref(kpad)))
+    return arrs[0], arrs[1], arrs[2], arrs[3], kp.value, kpad.value
+
+
 def fq_threshold_boxplot(chmax: np.ndarray, beta: float = 1.3) -> float:
     """Host call (Eq. 6-7).  Returns T as a Python float holding an fp32 value."""
     chmax = np.ascontiguousarray(chmax, dtype=np.float32)
@@ -181,6 +205,27 @@ def fq_flatten_weights(W, src_idx, bits: int, Wq_out, s_w_out, workspace, stream
     _check(lib().fq_flatten_weights(W.data_ptr(), _dtype_code(W), N, K, W.stride(0), src_idx.data_ptr(), Kpad, bits,
                                     Wq_out.data_ptr(), s_w_out.data_ptr(), workspace.data_ptr(),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fq_flatten_weights_split(W, src_idx, rep_w, bits: int, Wq_out, s_w_out, workspace, stream=None) -> None:
+    _dev2d(W, "W")
+    N, K = W.shape
+    Kpad = src_idx.numel()
+    _check(lib().fq_flatten_weights_split(W.data_ptr(), _dtype_code(W), N, K, W.stride(0), src_idx.data_ptr(),
+                                          rep_w.data_ptr(), Kpad, bits, Wq_out.data_ptr(), s_w_out.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream(stream)))
+
+
+def fq_flatten_quant_act_peel(X, src_idx, ord, bits: int, T: float, Xq_out, s_x_out, workspace, absmax_in=None,
+                              stream=None) -> None:
+    _dev2d(X, "X")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    _check(lib().fq_flatten_quant_act_peel(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(),
+                                           ord.data_ptr(), Kpad, bits, T, _ptr(absmax_in), Xq_out.data_ptr(),
+                                           s_x_out.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def fq_flatten_quant_act(X, src_idx, rep, bits: int, Xq_out, s_x_out, workspace, absmax_in=None, stream=None) -> None:

@@ -128,6 +128,52 @@ int fq_flatten_plan(const float* chmax_host, int K, float T, int align, int32_t*
     return FQ_OK;
 }
 
+int fq_flatten_plan_xw(const float* chmax_x_host, float T_x, const float* chmax_w_host, float T_w, int K, int align,
+                       int32_t* src_idx_host, int32_t* rep_x_host, int32_t* rep_w_host, int32_t* ord_host, int cap,
+                       int* Kprime_out, int* Kpad_out)
+{
+    clear_error();
+    if (!chmax_x_host) return fail(FQ_ERR_NULL, "chmax_x is NULL");
+    if (K <= 0 || align <= 0 || cap < 0) return fail(FQ_ERR_SHAPE, "K = %d, align = %d, cap = %d", K, align, cap);
+    if (!(T_x > 0.0f) || std::isinf(T_x)) return fail(FQ_ERR_RANGE, "T_x = %g must be positive and finite", (double)T_x);
+    if (chmax_w_host && (!(T_w > 0.0f) || std::isinf(T_w)))
+        return fail(FQ_ERR_RANGE, "T_w = %g must be positive and finite", (double)T_w);
+    // shares of channel j on either side; 0 reports an invalid maximum
+    auto shares = [](float c, float T) -> long long {
+        if (!(c >= 0.0f) || std::isinf(c)) return 0;
+        const double n = std::ceil((double)c / (double)T);
+        return n > 1.0 ? (n > 1.0e9 ? (long long)1e9 : (long long)n) : 1;
+    };
+    long long total = 0;
+    for (int j = 0; j < K; ++j) {
+        const long long nx = shares(chmax_x_host[j], T_x), nw = chmax_w_host ? shares(chmax_w_host[j], T_w) : 1;
+        if (nx == 0 || nw == 0) return fail(FQ_ERR_RANGE, "channel maximum %d must be finite and >= 0", j);
+        total += nx * nw;
+        if (total > (1LL << 30)) return fail(FQ_ERR_RANGE, "flattened width exceeds 2^30 channels");
+    }
+    const long long Kpad = (total + align - 1) / align * align;
+    if (Kpad > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "padded width exceeds int32");
+    if (Kprime_out) *Kprime_out = (int)total;
+    if (Kpad_out) *Kpad_out = (int)Kpad;
+    if (cap == 0) return FQ_OK;
+    if (!src_idx_host || !rep_x_host) return fail(FQ_ERR_NULL, "src_idx / rep_x is NULL with cap > 0");
+    if (cap < Kpad) return fail(FQ_ERR_SHAPE, "cap = %d < Kpad = %lld", cap, Kpad);
+    auto put = [&](int p, int j, int nx, int nw, int e) {
+        src_idx_host[p] = j;
+        rep_x_host[p] = nx;
+        if (rep_w_host) rep_w_host[p] = nw;
+        if (ord_host) ord_host[p] = e;
+    };
+    int tail = K;
+    for (int j = 0; j < K; ++j) {
+        const int nx = (int)shares(chmax_x_host[j], T_x), nw = chmax_w_host ? (int)shares(chmax_w_host[j], T_w) : 1;
+        put(j, j, nx, nw, 0);
+        for (int e = 1; e < nx * nw; ++e) put(tail++, j, nx, nw, e);
+    }
+    for (; tail < (int)Kpad; ++tail) put(tail, -1, 0, 0, 0);
+    return FQ_OK;
+}
+
 int fq_threshold_boxplot(const float* chmax_host, int K, float beta, float* T_out_host)
 {
     clear_error();
@@ -243,6 +289,35 @@ int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx, cons
     ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
     return launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in,
                                 Xq_out, s_x_out, ws, static_cast<hipStream_t>(stream));
+}
+
+int fq_flatten_weights_split(const void* W, int w_dtype, int N, int K, int ldw, const int32_t* src_idx,
+                             const int32_t* rep_w, int Kpad, int bits, void* Wq_out, float* s_w_out, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    // the equal split applied to the weight array: the activation path with the weights' share counts
+    return fq_flatten_quant_act(W, w_dtype, N, K, ldw, src_idx, rep_w, Kpad, bits, nullptr, Wq_out, s_w_out, workspace,
+                                workspace_bytes, stream);
+}
+
+int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx,
+                              const int32_t* ord, int Kpad, int bits, float T, const float* absmax_in, void* Xq_out,
+                              float* s_x_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_matrix("X", X, x_dtype, M, K, ldx);
+    if (rc) return rc;
+    rc = check_map(src_idx, Kpad, bits);
+    if (rc) return rc;
+    if (!(T > 0.0f) || std::isinf(T)) return fail(FQ_ERR_RANGE, "T = %g must be positive and finite", (double)T);
+    if (!ord || !Xq_out || !s_x_out || !workspace) return fail(FQ_ERR_NULL, "ord, Xq_out, s_x_out or workspace is NULL");
+    if (!aligned16(Xq_out) || !aligned16(workspace)) return fail(FQ_ERR_ALIGN, "Xq_out or workspace is not 16-byte aligned");
+    if (workspace_bytes < fq_act_workspace_bytes(K, Kpad))
+        return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
+                    fq_act_workspace_bytes(K, Kpad));
+    ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
+    return launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, ord, Kpad, bits, absmax_in ? 4 : 3, absmax_in, Xq_out,
+                                s_x_out, ws, static_cast<hipStream_t>(stream), T);
 }
 
 int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,

@@ -35,11 +35,13 @@ struct ActWorkspace {
 ActWorkspace carve_act_workspace(void* base, int K, int Kpad);
 
 // ---- launchers (each validates nothing: the C-ABI layer has already done so) ----
-// mode 0: activation, dynamic absmax; 1: activation, static absmax (*absmax_in); 2: weights
+// mode 0: equal split, dynamic absmax; 1: equal split, static absmax (*absmax_in); 2: weights (rep
+// ignored, every slot a plain copy); 3 / 4: the printed peel split with threshold T, dynamic / static
+// absmax, `rep` then carrying the slot ordinals
 int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld,
                          const int32_t* src_idx, const int32_t* rep, int Kpad, int bits,
                          int mode, const float* absmax_in, void* out, float* scale_out,
-                         const ActWorkspace& ws, hipStream_t stream);
+                         const ActWorkspace& ws, hipStream_t stream, float T = 0.0f);
 
 // chmax[j] = max(start, max_i |X[i, j]|), start = 0 or (accumulate) the non-negative value held on entry
 int launch_channel_absmax(const void* X, int x_dtype, int M, int K, int ld, int accumulate, float* chmax,

@@ -188,10 +188,49 @@ __device__ __forceinline__ Quot wave_quot_max(Quot q)
 __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict__ cmax, int K,
                                                      const int32_t* __restrict__ src,
                                                      const int32_t* __restrict__ rep, int Kpad, int qmax,
-                                                     int mode, const float* __restrict__ absmax_in,
+                                                     int mode, const float* __restrict__ absmax_in, float T,
                                                      float* __restrict__ mslot, float* __restrict__ scale_out,
                                                      float* __restrict__ scalars)
 {
+    // Peel split (modes 3 dynamic / 4 static): `rep` carries the slot ordinals e; mslot[p] receives the
+    // offset fl32(e * T) that the slot subtracts from |x| (+inf in padding, which clamps to 0), and the
+    // single multiplier m = fl32(qmax / a') goes to scalars[1].  a' = min(T, max_j cmax[j]) when dynamic.
+    if (mode >= 3) {
+        __shared__ float redf[16];
+        __shared__ float a_peel;
+        const int tid = threadIdx.x;
+        float a;
+        if (mode == 3) {
+            float best = 0.0f;
+            for (int j = tid; j < K; j += 1024) best = fmaxf(best, __uint_as_float(cmax[j]));
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off, 64));
+            if ((tid & 63) == 0) redf[tid >> 6] = best;
+            __syncthreads();
+            if (tid == 0) {
+                float t = 0.0f;
+                for (int w = 0; w < 16; ++w) t = fmaxf(t, redf[w]);
+                a_peel = fminf(t, T);
+            }
+            __syncthreads();
+            a = a_peel;
+        } else {
+            a = *absmax_in;
+            if (!(a >= 0.0f) || a > 3.0e38f) a = 0.0f;
+        }
+        if (blockIdx.x == 0 && tid == 0) {
+            *scale_out = (a == 0.0f) ? 1.0f : (float)((double)a / (double)qmax);
+            scalars[0] = a;
+            scalars[1] = (a == 0.0f) ? 0.0f : (float)((double)qmax / (double)a);
+        }
+        const int p = blockIdx.x * 1024 + tid;
+        if (p < Kpad) {
+            const int sp = src[p], e = rep[p];
+            const bool valid = (unsigned)sp < (unsigned)K && e >= 0;
+            mslot[p] = valid ? (float)e * T : __builtin_inff();
+        }
+        return;
+    }
     __shared__ Quot red[16];
     __shared__ float a_shared;
     __shared__ float table[1024];
@@ -252,11 +291,16 @@ template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
     return (int)r;
 }
 
-template <int DT, int BITS>
+// PEEL = false: slot value x * m_p (equal split; m_p from mslot).  PEEL = true: the printed split of
+// Eq. 3, slot value sign(x) * clamp(|x| - t_p, 0, thr) times the single multiplier scalars[1], with the
+// offsets t_p in mslot.
+template <int DT, int BITS, bool PEEL = false>
 __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restrict__ Xv, int M, int K, int ld,
                                                             const int32_t* __restrict__ src,
                                                             const float* __restrict__ mslot, int Kpad,
-                                                            int rows_per_thread, uint8_t* __restrict__ out)
+                                                            int rows_per_thread, uint8_t* __restrict__ out,
+                                                            const float* __restrict__ scalars = nullptr,
+                                                            float thr = 0.0f)
 {
     typedef typename Elem<DT>::type T;
     constexpr int VEC = Elem<DT>::VEC;
@@ -289,10 +333,16 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     bool contig = (s[0] >= 0) && (s[0] % VEC == 0) && (s[0] + 15 < K);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        if ((unsigned)s[i] >= (unsigned)K) { s[i] = 0; m[i] = 0.0f; contig = false; }   // padding / invalid
+        if ((unsigned)s[i] >= (unsigned)K) {                                            // padding / invalid
+            s[i] = 0;
+            m[i] = PEEL ? __builtin_inff() : 0.0f;
+            contig = false;
+        }
         if (s[i] != s[0] + i) contig = false;
     }
 
+    float mq = 0.0f;
+    if constexpr (PEEL) mq = scalars[1];
     const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
     uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
     const T* row = X + (size_t)r0 * ld;
@@ -313,7 +363,14 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
         }
         int q[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(x[i], m[i]);
+        for (int i = 0; i < 16; ++i) {
+            if constexpr (PEEL) {
+                const float mag = fminf(fmaxf(fabsf(x[i]) - m[i], 0.0f), thr);
+                q[i] = quant1<BITS>(x[i] < 0.0f ? -mag : mag, mq);
+            } else {
+                q[i] = quant1<BITS>(x[i], m[i]);
+            }
+        }
         if (BITS == 8) {
             v4u w;
 #pragma unroll
@@ -355,25 +412,29 @@ void launch_colabsmax(const void* X, int M, int K, int ld, bool accumulate, uint
 
 template <int DT>
 int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx, const int32_t* rep,
-                     int Kpad, int bits, int mode, const float* absmax_in, void* out, float* scale_out,
+                     int Kpad, int bits, int mode, const float* absmax_in, float T, void* out, float* scale_out,
                      const ActWorkspace& ws, hipStream_t stream)
 {
     const int qmax = (1 << (bits - 1)) - 1;
-    if (mode != 1) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
-    scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, ws.mslot,
-                                         scale_out, ws.scalars);
+    const bool peel = mode >= 3;
+    if (mode != 1 && mode != 4) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
+    scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, T,
+                                                            ws.mslot, scale_out, ws.scalars);
     const int G = Kpad / 16;
     // rows per thread: as many as 8 while the launch still has >= 2048 waves
     int rpt = 8;
     while (rpt > 1 && ((long long)G * ((M + rpt - 1) / rpt)) < 2048LL * 64) rpt >>= 1;
     const long long threads = (long long)G * ((M + rpt - 1) / rpt);
     const unsigned blocks = (unsigned)((threads + 255) / 256);
-    if (bits == 8)
-        flatten_quant_kernel<DT, 8><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt,
-                                                                static_cast<uint8_t*>(out));
+    uint8_t* o8 = static_cast<uint8_t*>(out);
+    if (peel && bits == 8)
+        flatten_quant_kernel<DT, 8, true><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt, o8, ws.scalars, T);
+    else if (peel)
+        flatten_quant_kernel<DT, 4, true><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt, o8, ws.scalars, T);
+    else if (bits == 8)
+        flatten_quant_kernel<DT, 8><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt, o8);
     else
-        flatten_quant_kernel<DT, 4><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt,
-                                                                static_cast<uint8_t*>(out));
+        flatten_quant_kernel<DT, 4><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt, o8);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "flatten-quantize launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
@@ -398,15 +459,15 @@ ActWorkspace carve_act_workspace(void* base, int K, int Kpad)
 
 int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld, const int32_t* src_idx,
                          const int32_t* rep, int Kpad, int bits, int mode, const float* absmax_in,
-                         void* out, float* scale_out, const ActWorkspace& ws, hipStream_t stream)
+                         void* out, float* scale_out, const ActWorkspace& ws, hipStream_t stream, float T)
 {
     switch (x_dtype) {
     case FQ_F32:
-        return launch_for_dtype<FQ_F32>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+        return launch_for_dtype<FQ_F32>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, T, out, scale_out, ws, stream);
     case FQ_F16:
-        return launch_for_dtype<FQ_F16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+        return launch_for_dtype<FQ_F16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, T, out, scale_out, ws, stream);
     case FQ_BF16:
-        return launch_for_dtype<FQ_BF16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, out, scale_out, ws, stream);
+        return launch_for_dtype<FQ_BF16>(X, M, K, ld, src_idx, rep, Kpad, bits, mode, absmax_in, T, out, scale_out, ws, stream);
     default:
         return fail(FQ_ERR_DTYPE, "unsupported input dtype %d", x_dtype);
     }

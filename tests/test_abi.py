@@ -145,3 +145,24 @@ def test_policy_helpers_match_oracle(seed):
         fq.fq_threshold_boxplot(cx, -1.0)
     with pytest.raises(fq.FqError):
         fq.fq_smooth_scales(cx, cw, 2.0)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_xw_matches_oracle(seed):
+    """Two-sided plan (Sec. 4.1): the library's host function against the oracle, with and without weight maxima."""
+    rng = np.random.default_rng(200 + seed)
+    K = int(rng.integers(1, 600))
+    cx = (np.abs(rng.standard_normal(K)) * rng.choice([1, 1, 1, 25], K)).astype(np.float32)
+    cw = (np.abs(rng.standard_normal(K)) * 0.1 * rng.choice([1, 1, 4], K)).astype(np.float32)
+    T_x, T_w = float(np.float32(rng.uniform(0.5, 4))), float(np.float32(rng.uniform(0.05, 0.3)))
+    align = int(rng.choice([1, 32, 128, 256]))
+    for w in (None, cw):
+        got = fq.fq_flatten_plan_xw(cx, T_x, w, T_w, align)
+        ref = O.plan_xw(cx, T_x, w, T_w, align)
+        assert got[4:] == ref[4:]
+        for a, b in zip(got[:4], ref[:4]):
+            np.testing.assert_array_equal(a, b)
+    with pytest.raises(fq.FqError):
+        fq.fq_flatten_plan_xw(cx, 0.0)
+    with pytest.raises(fq.FqError):
+        fq.fq_flatten_plan_xw(cx, 1.0, cw, float("inf"))

@@ -366,3 +366,81 @@ def test_bmm_variants_and_padded_strides(variant):
     assert rel_err(got, y_ref).max() <= 2.0 ** -8
     full = Ybuf.float().cpu().numpy()
     assert (full[:, M:, :] == 99.0).all() and (full[:, :, N:] == 99.0).all()
+
+
+# ------------------------------------------------------------------------------------------
+# Eq. 3 as printed (peel split) and weight-side flattening
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("static", [False, True])
+@pytest.mark.parametrize("cfg,over", [
+    ("cfg1", {}),
+    ("cfg2", dict(M_override=333, K_override=1000, N_override=8)),
+    ("cfg3", dict(M_override=517, K_override=2048, N_override=8)),
+])
+def test_flatten_quant_act_peel(cfg, over, static, bits):
+    L = _layer(cfg, **over)
+    if L.spec.x_dtype != "f32" and L.X.shape[1] % 8:
+        pytest.skip("row stride must be a multiple of 16 bytes")
+    M, K = L.X.shape
+    T = float(np.float32(L.T))
+    src, rx, rw, od, kp, kpad = fq.fq_flatten_plan_xw(L.chmax, T)
+    a_ref = np.float32(T) if static else O.act_absmax_peel(L.X, T)
+    q_ref, s_ref = O.flatten_quant_act_peel(L.X, src, od, bits, T, a_ref)
+    want = q_ref.view(np.uint8) if bits == 8 else O.pack_i4(q_ref)
+    Xd = to_dev(L.X_store, L.spec.x_dtype)
+    out = torch.full((M, kpad if bits == 8 else kpad // 2), 0x55, dtype=torch.uint8, device=DEV)
+    s_x = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = bytes_ws(fq.fq_act_workspace_bytes(K, kpad))
+    fq.fq_flatten_quant_act_peel(Xd, dev_i32(src), dev_i32(od), bits, T, out, s_x, ws,
+                                 absmax_in=scalar(T) if static else None)
+    torch.cuda.synchronize()
+    assert np.float32(s_x.item()) == s_ref
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_two_sided_flatten_end_to_end(bits):
+    """Weights' own channels split (fq_flatten_weights_split) together with the activation split over
+    the two-sided map: quantized tensors and accumulators bit-exact, output close to the float layer."""
+    L = _layer("cfg3", M_override=300, K_override=1024, N_override=200)
+    M, K = L.X.shape
+    N = L.W.shape[0]
+    rng = np.random.default_rng(9)
+    W = L.W.copy()
+    W[:, rng.choice(K, 12, replace=False)] *= np.float32(5.0)               # a few large weight channels
+    W_store, W = WL.round_to_dtype(W, L.spec.w_dtype)                       # 5x is exact only up to rounding
+    cw = np.abs(W).max(axis=0)
+    T_w = float(np.float32(2.0 * np.median(cw)))
+    src, rx, rw, od, kp, kpad = fq.fq_flatten_plan_xw(L.chmax, float(L.T), cw, T_w, align=128 if bits == 8 else 256)
+    assert (rw > 1).any() and (rx > 1).any()
+    Wq_ref, s_w_ref = O.flatten_weights_split(W, src, rw, bits)
+    Xq_ref, s_x_ref = O.flatten_quant_act(L.X, src, rx, bits, O.act_absmax_dynamic(L.X, src, rx))
+    acc_ref = O.gemm_i32(Xq_ref, Wq_ref)
+    cols = kpad if bits == 8 else kpad // 2
+    Wd = to_dev(W_store, L.spec.w_dtype)
+    Xd = to_dev(L.X_store, L.spec.x_dtype)
+    Wq = torch.empty((N, cols), dtype=torch.uint8, device=DEV)
+    Xq = torch.empty((M, cols), dtype=torch.uint8, device=DEV)
+    s_w, s_x = scalar(0.0), scalar(0.0)
+    ws = bytes_ws(fq.fq_act_workspace_bytes(K, kpad))
+    srcd = dev_i32(src)
+    fq.fq_flatten_weights_split(Wd, srcd, dev_i32(rw), bits, Wq, s_w, ws)
+    fq.fq_flatten_quant_act(Xd, srcd, dev_i32(rx), bits, Xq, s_x, ws)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    gemm = fq.fq_gemm_i8 if bits == 8 else fq.fq_gemm_i4
+    Xv, Wv = (Xq.view(torch.int8), Wq.view(torch.int8)) if bits == 8 else (Xq, Wq)
+    gemm(Xv, Wv, None, None, acc)
+    gemm(Xv, Wv, s_x, s_w, y)
+    torch.cuda.synchronize()
+    assert np.float32(s_w.item()) == s_w_ref and np.float32(s_x.item()) == s_x_ref
+    np.testing.assert_array_equal(Wq.cpu().numpy(), Wq_ref.view(np.uint8) if bits == 8 else O.pack_i4(Wq_ref))
+    np.testing.assert_array_equal(Xq.cpu().numpy(), Xq_ref.view(np.uint8) if bits == 8 else O.pack_i4(Xq_ref))
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_ref)
+    y_ref = O.dequant(acc_ref, s_x_ref, s_w_ref)
+    assert rel_err(y.cpu().numpy().astype(np.float64), y_ref).max() <= 1e-6
+    # and the quantized layer tracks the float layer (INT8 closely, INT4 loosely)
+    y_float = O.linear_f64(L.X, W)
+    err = np.sqrt(np.mean((y_ref - y_float) ** 2)) / np.sqrt(np.mean(y_float ** 2))
+    assert err < (0.03 if bits == 8 else 0.4)
