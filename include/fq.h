@@ -218,6 +218,19 @@ int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad,
 int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad,
                const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy, void* stream);
 
+/* fq_gemm_i8_bias / fq_gemm_i4_bias / fq_linear_bias — the same calls with the layer's bias folded
+ * into the epilogue (the paper's quantized layer replaces OPT's linear layers, which carry one; it
+ * does not spell the bias out, the reading taken: added in floating point after dequantization):
+ *   Y[i,n] = round_to_y_dtype( fl32( fl32(fl32(acc[i,n]) * fl32(*s_x * *s_w)) + bias[n] ) ).
+ * bias  fp32 [N], device, 16-byte aligned; NULL gives exactly the calls above.  Not allowed with
+ *       FQ_I32 output (FQ_ERR_DTYPE). */
+int fq_gemm_i8_bias(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad,
+                    const float* s_x, const float* s_w, const float* bias,
+                    void* Y, int y_dtype, int ldy, void* stream);
+int fq_gemm_i4_bias(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad,
+                    const float* s_x, const float* s_w, const float* bias,
+                    void* Y, int y_dtype, int ldy, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * fq_bmm_i8 / fq_bmm_i4 — the batched form of the integer GEMM (Sec. 5.1: the quantized BMM function
  * that stands beside the quantized linear layer, for attention's two products).  The paper gives
@@ -252,6 +265,11 @@ int fq_linear(const void* X, int x_dtype, int M, int K, int ldx,
               const void* Wq, const float* s_w, int N, int bits,
               const float* absmax_in, void* Y, int y_dtype, int ldy,
               void* workspace, size_t workspace_bytes, void* stream);
+int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx,
+                   const int32_t* src_idx, const int32_t* rep, int Kpad,
+                   const void* Wq, const float* s_w, const float* bias, int N, int bits,
+                   const float* absmax_in, void* Y, int y_dtype, int ldy,
+                   void* workspace, size_t workspace_bytes, void* stream);
 size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits);
 
 /* ---------------------------------------------------------------------------------------------

@@ -656,3 +656,16 @@ int fqo_flatten_quant_act_peel(const float *X, int M, int K, int ldx, const int3
         }
     return FQO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Dequantize with the layer's bias: y[i, n] = acc[i, n] * s_x * s_w + bias[n], float64.  (The
+ * paper replaces OPT's linear layers, which carry a bias, by quantized ones without spelling the
+ * bias out; reading taken: it is added in floating point after the dequantization.)
+ * ---------------------------------------------------------------------------------------- */
+void fqo_dequant_bias(const int32_t *acc, int rows, int N, float s_x, float s_w, const float *bias,
+                      double *y_out)
+{
+    for (int i = 0; i < rows; ++i)
+        for (int n = 0; n < N; ++n)
+            y_out[(size_t)i * N + n] = (double)acc[(size_t)i * N + n] * (double)s_x * (double)s_w + (double)bias[n];
+}

@@ -329,3 +329,14 @@ def flatten_quant_act_peel(X, src, ord_, bits, T, a_prime):
                                           ctypes.c_float(a_prime), _p(out, ctypes.c_int8), ctypes.byref(s_x))
     _check(rc, "fqo_flatten_quant_act_peel")
     return out, np.float32(s_x.value)
+
+
+def dequant_bias(acc, s_x, s_w, bias):
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    rows, N = acc.shape
+    bias = _f32(bias)
+    assert bias.shape == (N,)
+    out = np.empty((rows, N), dtype=np.float64)
+    lib().fqo_dequant_bias(_p(acc, ctypes.c_int32), rows, N, ctypes.c_float(s_x), ctypes.c_float(s_w),
+                           _p(bias, ctypes.c_float), _p(out, ctypes.c_double))
+    return out

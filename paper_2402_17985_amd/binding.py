@@ -23,7 +23,8 @@ SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_
            "fq_weights_workspace_bytes", "fq_flatten_quant_act", "fq_act_workspace_bytes", "fq_gemm_i8",
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
            "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
-           "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel"]
+           "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel",
+           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias"]
 
 
 class FqError(RuntimeError):
@@ -71,6 +72,10 @@ def lib() -> ctypes.CDLL:
     for f in (L.fq_bmm_i8, L.fq_bmm_i4):
         f.argtypes = [vp, vp, c_int, c_int, c_int, c_int, ctypes.c_longlong, ctypes.c_longlong, vp, vp, vp, c_int,
                       c_int, ctypes.c_longlong, vp]
+    for f in (L.fq_gemm_i8_bias, L.fq_gemm_i4_bias):
+        f.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, c_int, c_int, vp]
+    L.fq_linear_bias.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, vp, c_int, c_int, vp, vp,
+                                 c_int, c_int, vp, c_size_t, vp]
     L.fq_linear.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, c_int, c_int, vp, vp, c_int,
                             c_int, vp, c_size_t, vp]
     L.fq_linear_workspace_bytes.restype = c_size_t
@@ -249,6 +254,38 @@ def fq_gemm_i8(Xq, Wq, s_x, s_w, Y, stream=None) -> None:
     M, Kpad = Xq.shape
     N = Wq.shape[0]
     _gemm(lib().fq_gemm_i8, Xq, Wq, M, N, Kpad, s_x, s_w, Y, stream)
+
+
+def _gemm_bias(fn, Xq, Wq, M, N, Kpad, s_x, s_w, bias, Y, stream):
+    _dev2d(Y, "Y")
+    if bias is not None and (bias.numel() != N or _dtype_code(bias) != FQ_F32 or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous fp32 tensor of N elements")
+    _check(fn(Xq.data_ptr(), Wq.data_ptr(), M, N, Kpad, _ptr(s_x), _ptr(s_w), _ptr(bias), Y.data_ptr(), _dtype_code(Y),
+              Y.stride(0), _stream(stream)))
+
+
+def fq_gemm_i8_bias(Xq, Wq, s_x, s_w, bias, Y, stream=None) -> None:
+    M, Kpad = Xq.shape
+    _gemm_bias(lib().fq_gemm_i8_bias, Xq, Wq, M, Wq.shape[0], Kpad, s_x, s_w, bias, Y, stream)
+
+
+def fq_gemm_i4_bias(Xq, Wq, s_x, s_w, bias, Y, stream=None) -> None:
+    M, half = Xq.shape
+    _gemm_bias(lib().fq_gemm_i4_bias, Xq, Wq, M, Wq.shape[0], 2 * half, s_x, s_w, bias, Y, stream)
+
+
+def fq_linear_bias(X, src_idx, rep, Wq, s_w, bias, bits: int, Y, workspace, absmax_in=None, stream=None) -> None:
+    _dev2d(X, "X")
+    _dev2d(Y, "Y")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    N = Wq.shape[0]
+    if bias is not None and (bias.numel() != N or _dtype_code(bias) != FQ_F32 or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous fp32 tensor of N elements")
+    _check(lib().fq_linear_bias(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(), rep.data_ptr(),
+                                Kpad, Wq.data_ptr(), s_w.data_ptr(), _ptr(bias), N, bits, _ptr(absmax_in), Y.data_ptr(),
+                                _dtype_code(Y), Y.stride(0), workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def fq_gemm_i4(Xq, Wq, s_x, s_w, Y, stream=None) -> None:

@@ -7,7 +7,12 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfq.so")
-SOURCES = ["fq_api.hip", "fq_quant.hip", "fq_gemm.hip"]
+# (source, extra flags, object name); fq_gemm.hip is built once per operand mode, in parallel
+SOURCES = [("fq_gemm.hip", ["-DFQ_GEMM_MODE=1"], "fq_gemm_i4.o"),
+           ("fq_gemm.hip", ["-DFQ_GEMM_MODE=0"], "fq_gemm_i8.o"),
+           ("fq_gemm.hip", ["-DFQ_GEMM_MODE=2"], "fq_gemm_bf16.o"),
+           ("fq_api.hip", [], "fq_api.o"), ("fq_quant.hip", [], "fq_quant.o"),
+           ("fq_gemm_select.hip", [], "fq_gemm_select.o")]
 # -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions
 # -ffp-contract=off: every fp32 multiply stays a single correctly rounded operation
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -31,16 +36,17 @@ def _newer(target, deps):
 
 def build(force: bool = True, verbose: bool = False) -> str:
     hdrs = [os.path.join(CSRC, "fq_internal.h"), os.path.join(HERE, "..", "include", "fq.h")]
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    if not force and _newer(OUT, srcs + hdrs):
+    srcs = [(os.path.join(CSRC, s), extra, obj) for s, extra, obj in SOURCES]
+    if not force and _newer(OUT, [s for s, _, _ in srcs] + hdrs):
         return OUT
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
-    def compile_one(src):
-        obj = os.path.join(objdir, os.path.basename(src) + ".o")
-        cmd = [hipcc] + FLAGS + ["-c", src, "-o", obj]
+    def compile_one(item):
+        src, extra, objname = item
+        obj = os.path.join(objdir, objname)
+        cmd = [hipcc] + FLAGS + extra + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -22,7 +22,6 @@ int fail(int code, const char* fmt, ...)
 }
 void clear_error() { g_err[0] = '\0'; }
 
-int set_gemm_variant(int v);   // fq_gemm.hip
 
 namespace {
 
@@ -320,22 +319,49 @@ int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx,
                                 s_x_out, ws, static_cast<hipStream_t>(stream), T);
 }
 
-int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
-               void* Y, int y_dtype, int ldy, void* stream)
+namespace {
+int check_bias(const float* bias, int y_dtype)
+{
+    if (!bias) return FQ_OK;
+    if (y_dtype == FQ_I32) return fail(FQ_ERR_DTYPE, "a bias cannot be added to raw int32 accumulators");
+    if (!aligned16(bias)) return fail(FQ_ERR_ALIGN, "bias is not 16-byte aligned");
+    return FQ_OK;
+}
+
+int gemm_common(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits, const float* s_x, const float* s_w,
+                const float* bias, void* Y, int y_dtype, int ldy, void* stream)
 {
     clear_error();
     int rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
     if (rc) return rc;
-    return launch_gemm_int(Xq, Wq, M, N, Kpad, 8, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream));
+    rc = check_bias(bias, y_dtype);
+    if (rc) return rc;
+    return launch_gemm_int(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream), bias);
+}
+}  // namespace
+
+int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+               void* Y, int y_dtype, int ldy, void* stream)
+{
+    return gemm_common(Xq, Wq, M, N, Kpad, 8, s_x, s_w, nullptr, Y, y_dtype, ldy, stream);
 }
 
 int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
                void* Y, int y_dtype, int ldy, void* stream)
 {
-    clear_error();
-    int rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
-    if (rc) return rc;
-    return launch_gemm_int(Xq, Wq, M, N, Kpad, 4, s_x, s_w, Y, y_dtype, ldy, static_cast<hipStream_t>(stream));
+    return gemm_common(Xq, Wq, M, N, Kpad, 4, s_x, s_w, nullptr, Y, y_dtype, ldy, stream);
+}
+
+int fq_gemm_i8_bias(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+                    const float* bias, void* Y, int y_dtype, int ldy, void* stream)
+{
+    return gemm_common(Xq, Wq, M, N, Kpad, 8, s_x, s_w, bias, Y, y_dtype, ldy, stream);
+}
+
+int fq_gemm_i4_bias(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+                    const float* bias, void* Y, int y_dtype, int ldy, void* stream)
+{
+    return gemm_common(Xq, Wq, M, N, Kpad, 4, s_x, s_w, bias, Y, y_dtype, ldy, stream);
 }
 
 namespace {
@@ -375,6 +401,15 @@ int fq_linear(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* 
               int Kpad, const void* Wq, const float* s_w, int N, int bits, const float* absmax_in, void* Y,
               int y_dtype, int ldy, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return fq_linear_bias(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, Wq, s_w, nullptr, N, bits, absmax_in, Y, y_dtype, ldy,
+                          workspace, workspace_bytes, stream);
+}
+
+int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx, const int32_t* rep,
+                   int Kpad, const void* Wq, const float* s_w, const float* bias, int N, int bits,
+                   const float* absmax_in, void* Y, int y_dtype, int ldy, void* workspace, size_t workspace_bytes,
+                   void* stream)
+{
     clear_error();
     int rc = check_matrix("X", X, x_dtype, M, K, ldx);
     if (rc) return rc;
@@ -392,11 +427,13 @@ int fq_linear(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* 
     float* s_x = ws.scalars + 1;
     rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
     if (rc) return rc;
+    rc = check_bias(bias, y_dtype);
+    if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in, Xq,
                               s_x, ws, st);
     if (rc) return rc;
-    return launch_gemm_int(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy, st);
+    return launch_gemm_int(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy, st, bias);
 }
 
 int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream)

@@ -39,6 +39,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 enum { MODE_I8 = 0, MODE_I4 = 1, MODE_BF16 = 2 };
@@ -68,13 +69,6 @@ __device__ __forceinline__ void dma16_addr(const uint8_t* lane_address, uint32_t
 
 // 16 zero bytes in device memory: the source of DMA lanes that fall beyond the end of a row.
 __device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
-
-// Batched launches: `count` independent problems, operand and output base addresses advancing by these
-// byte strides (count = 1, strides 0 for a single GEMM).
-struct Batch {
-    int count;
-    size_t stride_a, stride_b, stride_y;
-};
 
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
@@ -113,26 +107,44 @@ template <> struct OutVec<FQ_F32> { typedef float type __attribute__((ext_vector
 template <> struct OutVec<FQ_F16> { typedef _Float16 type __attribute__((ext_vector_type(4))); };
 template <> struct OutVec<FQ_BF16> { typedef __bf16 type __attribute__((ext_vector_type(4))); };
 
-template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typename Acc<MODE>::type const& acc, int r, float scale)
+// One output element: the accumulator scaled by s_x * s_w, plus (optionally) the column's bias, both
+// in fp32 as two separately rounded operations, then rounded to the output type.
+template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typename Acc<MODE>::type const& acc, int r, float scale,
+                                                                         bool has_bias = false, float b = 0.0f)
 {
     if constexpr (MODE == MODE_BF16) {
         return (__bf16)acc[r];
     } else {
         int v = acc[r];
         if (MODE == MODE_I4) v >>= 8;
-        if constexpr (YDT == FQ_I32) return v;
-        else if constexpr (YDT == FQ_F32) return (float)v * scale;
-        else if constexpr (YDT == FQ_BF16) return (__bf16)((float)v * scale);
-        else return (_Float16)((float)v * scale);
+        if constexpr (YDT == FQ_I32) {
+            return v;
+        } else {
+            float f = (float)v * scale;
+            if (has_bias) f += b;
+            if constexpr (YDT == FQ_F32) return f;
+            else if constexpr (YDT == FQ_BF16) return (__bf16)f;
+            else return (_Float16)f;
+        }
     }
+}
+
+// The four bias values of the columns col .. col + 3 (zeros when there is no bias).
+__device__ __forceinline__ v4f bias4(const float* __restrict__ bias, int col)
+{
+    v4f b = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (bias) b = *reinterpret_cast<const v4f*>(bias + col);
+    return b;
 }
 
 template <int MODE, int YDT, int FM, int FN, typename acc_t>
 __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N, float scale,
-                                              void* __restrict__ Y, int ldy, bool fast)
+                                              void* __restrict__ Y, int ldy, bool fast,
+                                              const float* __restrict__ bias = nullptr)
 {
     typedef typename OutVec<YDT>::type vec_t;
     typedef decltype(convert_out<MODE, YDT>(acc[0][0], 0, scale)) elem_t;
+    const bool hb = bias != nullptr;
     const int lane = threadIdx.x & 63;
     const int frow = lane & 31, fhalf = lane >> 5;
     elem_t* Yt = static_cast<elem_t*>(Y);
@@ -145,9 +157,10 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
+                    const v4f b4 = bias4(bias, col0 + 4 * fhalf + j * 32 + 8 * g);
                     vec_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale);
+                    for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
                     *reinterpret_cast<vec_t*>(yrow + j * 32 + 8 * g) = v;
                 }
         }
@@ -160,7 +173,8 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int col = col0 + j * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                    if (row < M && col < N) Yt[(size_t)row * ldy + col] = convert_out<MODE, YDT>(acc[i][j], r, scale);
+                    if (row < M && col < N)
+                        Yt[(size_t)row * ldy + col] = convert_out<MODE, YDT>(acc[i][j], r, scale, hb, hb ? bias[col] : 0.0f);
                 }
         }
     }
@@ -172,8 +186,10 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
 // per lane with 64/UNITS complete rows per instruction.  `stage` must hold FM*32 x FN*32 x 2 bytes.
 template <int MODE, int YDT, int FM, int FN, typename acc_t>
 __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row0, int col0, float scale,
-                                                   void* __restrict__ Y, int ldy, uint8_t* stage)
+                                                   void* __restrict__ Y, int ldy, uint8_t* stage,
+                                                   const float* __restrict__ bias = nullptr)
 {
+    const bool hb = bias != nullptr;
     typedef typename OutVec<YDT>::type vec_t;              // 4 x 2 bytes
     constexpr int ROWB = FN * 32 * 2;                      // bytes per staged row
     constexpr int UNITS = ROWB / 16;
@@ -189,9 +205,10 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
+                const v4f b4 = bias4(bias, col0 + 4 * fhalf + j * 32 + 8 * g);
                 vec_t v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale);
+                for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
                 const int u = g + 4 * j;
                 *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ (m & SW)) << 4) + 8 * fhalf) = v;
             }
@@ -210,7 +227,8 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
 template <int MODE, int FM, int FN, typename acc_t>
 __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N,
                                            const float* __restrict__ s_x, const float* __restrict__ s_w,
-                                           void* __restrict__ Y, int y_dtype, int ldy, uint8_t* stage = nullptr)
+                                           void* __restrict__ Y, int y_dtype, int ldy, uint8_t* stage = nullptr,
+                                           const float* __restrict__ bias = nullptr)
 {
     const bool fast = row0 + FM * 32 <= M && col0 + FN * 32 <= N && (ldy & 3) == 0 &&
                       (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
@@ -224,11 +242,11 @@ __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int c
             return;
         }
         const float scale = (*s_x) * (*s_w);
-        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
-        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
-        else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
-        else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
-        else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage, bias);
+        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage, bias);
+        else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+        else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+        else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
     }
 }
 
@@ -281,7 +299,8 @@ template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIP
 __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                               const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                               const float* __restrict__ s_x, const float* __restrict__ s_w,
-                                              void* __restrict__ Y, int y_dtype, int ldy)
+                                              void* __restrict__ Y, int y_dtype, int ldy,
+                                              const float* __restrict__ bias)
 {
     constexpr int NW = WM * WN;
     constexpr int CPR = BKB / 16;              // chunks per row per stage
@@ -584,7 +603,7 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
     // the final k-slice are in registers), so each wave may reuse its share of LDS to stage its output.
     constexpr bool CAN_STAGE = NW * TM * TN * 2 <= NSTAGE * STAGE;
     store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
-                             CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr);
+                             CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr, bias);
 }
 
 // The kernel.  Workgroups [0, n_main) compute full BM x BN tiles.  When the number of tiles leaves a
@@ -609,14 +628,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
     if (wg < n_main) {
         tile_of_workgroup(wg, n_main, tiles_m, tiles_n, tile_m, tile_n);
         gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
-                                                                s_x, s_w, Y, y_dtype, ldy);
+                                                                s_x, s_w, Y, y_dtype, ldy, bt.bias);
     } else {
         if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
             const int t = wg - n_main;
             tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
             gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM + (t & 1) * (BM / 2),
                                                                         tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
-                                                                        Y, y_dtype, ldy);
+                                                                        Y, y_dtype, ldy, bt.bias);
         }
     }
 }
@@ -728,11 +747,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
         __syncthreads();
     }
 
-    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy);
+    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy, nullptr, bt.bias);
 }
-
-// Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
-int g_variant = -1;
 
 int set_lds_limit(const void* kern, int smem, bool& attr_set)
 {
@@ -808,14 +824,12 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
     return FQ_OK;
 }
 
-constexpr int NUM_VARIANTS = 10;
-
 template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
              void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
     if (bt.count < 1 || bt.count > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", bt.count);
-    int v = g_variant;
+    int v = forced_gemm_variant();
     if (v < 0) {
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
         // short reductions (a few k-tiles) leave the output write as the bound: the smaller tile runs
@@ -839,34 +853,29 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
 
 }  // namespace
 
-int set_gemm_variant(int v)
+// This file is compiled once per operand mode (FQ_GEMM_MODE = 0 INT8, 1 packed INT4, 2 bf16), each
+// translation unit holding that mode's kernels and exporting its dispatcher.
+#ifndef FQ_GEMM_MODE
+#error "compile with -DFQ_GEMM_MODE=0, 1 or 2"
+#endif
+#if FQ_GEMM_MODE == 0
+int gemm_dispatch_i8(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                     void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
-    if (v < -1 || v >= NUM_VARIANTS) return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
-    g_variant = v;
-    return FQ_OK;
+    return dispatch<MODE_I8>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
 }
-
-int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits, const float* s_x,
-                    const float* s_w, void* Y, int y_dtype, int ldy, hipStream_t stream)
+#elif FQ_GEMM_MODE == 1
+int gemm_dispatch_i4(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                     void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
-    const Batch one = {1, 0, 0, 0};
-    if (bits == 8) return dispatch<MODE_I8>(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, one, stream);
-    return dispatch<MODE_I4>(Xq, Wq, M, N, Kpad / 2, s_x, s_w, Y, y_dtype, ldy, one, stream);
+    return dispatch<MODE_I4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
 }
-
-int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, size_t stride_a,
-                   size_t stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy,
-                   size_t stride_y_bytes, hipStream_t stream)
+#else
+int gemm_dispatch_bf16(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                       void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
-    const Batch bt = {batch, stride_a, stride_b, stride_y_bytes};
-    if (bits == 8) return dispatch<MODE_I8>(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy, bt, stream);
-    return dispatch<MODE_I4>(Aq, Bq, M, N, Kpad / 2, s_a, s_b, Y, y_dtype, ldy, bt, stream);
+    return dispatch<MODE_BF16>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
 }
-
-int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, hipStream_t stream)
-{
-    const Batch one = {1, 0, 0, 0};
-    return dispatch<MODE_BF16>(X, W, M, N, K * 2, nullptr, nullptr, Y, FQ_BF16, ldy, one, stream);
-}
+#endif
 
 }  // namespace fq

@@ -1,0 +1,45 @@
+// Kernel-variant selection and the entry points of the GEMM family: they forward to the per-mode
+// dispatchers, which live in the three translation units built from fq_gemm.hip.
+#include "fq_internal.h"
+
+namespace fq {
+
+namespace {
+constexpr int NUM_VARIANTS = 10;
+// Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
+int g_variant = -1;
+}  // namespace
+
+int forced_gemm_variant() { return g_variant; }
+
+int set_gemm_variant(int v)
+{
+    if (v < -1 || v >= NUM_VARIANTS) return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
+    g_variant = v;
+    return FQ_OK;
+}
+
+int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits, const float* s_x,
+                    const float* s_w, void* Y, int y_dtype, int ldy, hipStream_t stream, const float* bias)
+{
+    const Batch one = {1, 0, 0, 0, bias};
+    if (bits == 8) return gemm_dispatch_i8(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, one, stream);
+    return gemm_dispatch_i4(Xq, Wq, M, N, Kpad / 2, s_x, s_w, Y, y_dtype, ldy, one, stream);
+}
+
+int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, size_t stride_a,
+                   size_t stride_b, const float* s_a, const float* s_b, void* Y, int y_dtype, int ldy,
+                   size_t stride_y_bytes, hipStream_t stream)
+{
+    const Batch bt = {batch, stride_a, stride_b, stride_y_bytes, nullptr};
+    if (bits == 8) return gemm_dispatch_i8(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy, bt, stream);
+    return gemm_dispatch_i4(Aq, Bq, M, N, Kpad / 2, s_a, s_b, Y, y_dtype, ldy, bt, stream);
+}
+
+int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, hipStream_t stream)
+{
+    const Batch one = {1, 0, 0, 0, nullptr};
+    return gemm_dispatch_bf16(X, W, M, N, K * 2, nullptr, nullptr, Y, FQ_BF16, ldy, one, stream);
+}
+
+}  // namespace fq

@@ -47,9 +47,28 @@ int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld,
 int launch_channel_absmax(const void* X, int x_dtype, int M, int K, int ld, int accumulate, float* chmax,
                           hipStream_t stream);
 
+// Batched launches: `count` independent problems, operand and output base addresses advancing by these
+// byte strides (count = 1, strides 0 for a single GEMM); also carries the epilogue's optional bias.
+struct Batch {
+    int count;
+    size_t stride_a, stride_b, stride_y;
+    const float* bias;   // optional fp32 [N] added to the scaled accumulators (shared by the batch), or null
+};
+
+// Per-mode dispatchers (one translation unit each): A [M, rowbytes], B [N, rowbytes] bytes
+int gemm_dispatch_i8(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                     void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
+int gemm_dispatch_i4(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                     void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
+int gemm_dispatch_bf16(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                       void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
+int forced_gemm_variant();   // -1 = choose from the shape
+int set_gemm_variant(int v);
+
+// bias: optional fp32 [N] (16-byte aligned) added after scaling; must be null for FQ_I32 output
 int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits,
                     const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy,
-                    hipStream_t stream);
+                    hipStream_t stream, const float* bias = nullptr);
 
 // `batch` independent products; operand strides in bytes, stride_y_bytes in bytes
 int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad, int bits, size_t stride_a,

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
 {
     // Peel split (modes 3 dynamic / 4 static): `rep` carries the slot ordinals e; mslot[p] receives the
     // offset fl32(e * T) that the slot subtracts from |x| (+inf in padding, which clamps to 0), and the
-    // single multiplier m = fl32(qmax / a') goes to scalars[1].  a' = min(T, max_j cmax[j]) when dynamic.
+    // single multiplier m = fl32(qmax / a') goes to scalars[2].  a' = min(T, max_j cmax[j]) when dynamic.
     if (mode >= 3) {
         __shared__ float redf[16];
         __shared__ float a_peel;
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
         if (blockIdx.x == 0 && tid == 0) {
             *scale_out = (a == 0.0f) ? 1.0f : (float)((double)a / (double)qmax);
             scalars[0] = a;
-            scalars[1] = (a == 0.0f) ? 0.0f : (float)((double)qmax / (double)a);
+            scalars[2] = (a == 0.0f) ? 0.0f : (float)((double)qmax / (double)a);
         }
         const int p = blockIdx.x * 1024 + tid;
         if (p < Kpad) {
@@ -292,7 +292,7 @@ template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
 }
 
 // PEEL = false: slot value x * m_p (equal split; m_p from mslot).  PEEL = true: the printed split of
-// Eq. 3, slot value sign(x) * clamp(|x| - t_p, 0, thr) times the single multiplier scalars[1], with the
+// Eq. 3, slot value sign(x) * clamp(|x| - t_p, 0, thr) times the single multiplier scalars[2], with the
 // offsets t_p in mslot.
 template <int DT, int BITS, bool PEEL = false>
 __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restrict__ Xv, int M, int K, int ld,
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     }
 
     float mq = 0.0f;
-    if constexpr (PEEL) mq = scalars[1];
+    if constexpr (PEEL) mq = scalars[2];
     const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
     uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
     const T* row = X + (size_t)r0 * ld;

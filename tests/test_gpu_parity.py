@@ -444,3 +444,49 @@ def test_two_sided_flatten_end_to_end(bits):
     y_float = O.linear_f64(L.X, W)
     err = np.sqrt(np.mean((y_ref - y_float) ** 2)) / np.sqrt(np.mean(y_float ** 2))
     assert err < (0.03 if bits == 8 else 0.4)
+
+
+# ------------------------------------------------------------------------------------------
+# bias in the epilogue
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("ydt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("variant", [-1, 7, 2])
+def test_linear_bias(bits, ydt, variant):
+    """fq_linear_bias: y = acc * s_x * s_w + bias[n].  Tolerance: the product and the sum are each rounded
+    to fp32 (2^-24 of |product| and of |y|), then the output type's half ulp of |y|; measured against
+    |product| + |bias| so that cancellation between the two does not inflate the ratio."""
+    L = _layer("cfg3", M_override=300, K_override=1024, N_override=264)
+    M, K = L.X.shape
+    N = L.W.shape[0]
+    align = 128 if bits == 8 else 256
+    src, rep, kp, kpad = fq.fq_flatten_plan(L.chmax, L.T, align)
+    Wq_ref, s_w_ref = O.flatten_weights(L.W, src, bits)
+    acc_ref, _, s_x_ref = O.linear(L.X, src, rep, Wq_ref, s_w_ref, bits, want_y=False)
+    rng = np.random.default_rng(3)
+    prod = O.dequant(acc_ref, s_x_ref, s_w_ref)
+    bias = (rng.standard_normal(N) * np.sqrt(np.mean(prod ** 2))).astype(np.float32)
+    y_ref = O.dequant_bias(acc_ref, s_x_ref, s_w_ref, bias)
+    lay = fq.FqLinear(to_dev(L.W_store, L.spec.w_dtype), L.chmax, L.T, bits, device=DEV)
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[ydt]
+    Y = torch.full((M, N), 7.0, dtype=tdt, device=DEV)
+    ws = bytes_ws(fq.fq_linear_workspace_bytes(M, K, lay.Kpad, bits))
+    fq.fq_gemm_select(variant)
+    try:
+        fq.fq_linear_bias(to_dev(L.X_store, L.spec.x_dtype), lay.src, lay.rep, lay.Wq, lay.s_w,
+                          torch.from_numpy(bias).to(DEV), bits, Y, ws)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_gemm_select(-1)
+    got = Y.float().cpu().numpy().astype(np.float64)
+    tol = {"f32": 1e-6, "f16": 1e-3, "bf16": 2.0 ** -8}[ydt]
+    denom = np.abs(prod) + np.abs(bias.astype(np.float64))[None, :] + 1e-300
+    assert (np.abs(got - y_ref) / denom).max() <= tol
+    # a NULL bias is the plain call
+    Y0 = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    Y1 = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    X = to_dev(L.X_store, L.spec.x_dtype)
+    fq.fq_linear_bias(X, lay.src, lay.rep, lay.Wq, lay.s_w, None, bits, Y0, ws)
+    fq.fq_linear(X, lay.src, lay.rep, lay.Wq, lay.s_w, bits, Y1, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1)

@@ -147,3 +147,13 @@ def test_bmm_hand_case_and_library():
     got = O.bmm_i32(A, B)
     np.testing.assert_array_equal(got, ref)
     np.testing.assert_array_equal(O.bmm_i32(A[2:3], B[2:3])[0], O.gemm_i32(A[2], B[2]))
+
+
+def test_dequant_bias_hand_case():
+    """y = acc * s_x * s_w + bias[n]: exact binary fractions, so the float64 result is exact; the bias
+    goes with the column (a row/column mix-up changes the values)."""
+    acc = np.array([[4, -8, 0], [2, 2, 2]], dtype=np.int32)
+    y = O.dequant_bias(acc, np.float32(0.5), np.float32(0.25), np.array([1.0, -2.0, 0.5], np.float32))
+    assert y.tolist() == [[1.5, -3.0, 0.5], [1.25, -1.75, 0.75]]
+    np.testing.assert_array_equal(O.dequant_bias(acc, np.float32(0.3), np.float32(0.7), np.zeros(3, np.float32)),
+                                  O.dequant(acc, np.float32(0.3), np.float32(0.7)))
