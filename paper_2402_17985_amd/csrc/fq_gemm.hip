@@ -137,14 +137,13 @@ __device__ __forceinline__ v4f bias4(const float* __restrict__ bias, int col)
     return b;
 }
 
-template <int MODE, int YDT, int FM, int FN, typename acc_t>
+template <int MODE, int YDT, int FM, int FN, bool hb = false, typename acc_t>
 __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N, float scale,
                                               void* __restrict__ Y, int ldy, bool fast,
                                               const float* __restrict__ bias = nullptr)
 {
     typedef typename OutVec<YDT>::type vec_t;
     typedef decltype(convert_out<MODE, YDT>(acc[0][0], 0, scale)) elem_t;
-    const bool hb = bias != nullptr;
     const int lane = threadIdx.x & 63;
     const int frow = lane & 31, fhalf = lane >> 5;
     elem_t* Yt = static_cast<elem_t*>(Y);
@@ -157,7 +156,7 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const v4f b4 = bias4(bias, col0 + 4 * fhalf + j * 32 + 8 * g);
+                    const v4f b4 = bias4(hb ? bias : nullptr, col0 + 4 * fhalf + j * 32 + 8 * g);
                     vec_t v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
@@ -184,12 +183,11 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
 // memory sees full 128-byte row segments: the wave writes its tile as [row][column] (16-byte units
 // XOR-swizzled with the row to spread banks), reads it back 16 bytes per lane, and stores 16 bytes
 // per lane with 64/UNITS complete rows per instruction.  `stage` must hold FM*32 x FN*32 x 2 bytes.
-template <int MODE, int YDT, int FM, int FN, typename acc_t>
+template <int MODE, int YDT, int FM, int FN, bool hb = false, typename acc_t>
 __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row0, int col0, float scale,
                                                    void* __restrict__ Y, int ldy, uint8_t* stage,
                                                    const float* __restrict__ bias = nullptr)
 {
-    const bool hb = bias != nullptr;
     typedef typename OutVec<YDT>::type vec_t;              // 4 x 2 bytes
     constexpr int ROWB = FN * 32 * 2;                      // bytes per staged row
     constexpr int UNITS = ROWB / 16;
@@ -205,7 +203,7 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const v4f b4 = bias4(bias, col0 + 4 * fhalf + j * 32 + 8 * g);
+                const v4f b4 = bias4(hb ? bias : nullptr, col0 + 4 * fhalf + j * 32 + 8 * g);
                 vec_t v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
@@ -242,11 +240,20 @@ __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int c
             return;
         }
         const float scale = (*s_x) * (*s_w);
-        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage, bias);
-        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage, bias);
-        else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
-        else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
-        else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+        if (bias) {
+            // the biased epilogue is a separate instantiation so that the plain one carries none of it
+            if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN, true>(acc, row0, col0, scale, Y, ldy, stage, bias);
+            else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN, true>(acc, row0, col0, scale, Y, ldy, stage, bias);
+            else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+            else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+            else store_tile_as<MODE, FQ_F32, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
+            return;
+        }
+        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
+        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
+        else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+        else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+        else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
     }
 }
 
