@@ -283,7 +283,10 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  * fq_gemm_select — tuning hook for benchmarks: force the kernel variant used by fq_gemm_i8 /
  * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
  *   7: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the
- *      two waves of a SIMD alternate LDS-read and MFMA phases (the large-problem kernel)
+ *      two waves of a SIMD alternate LDS-read and MFMA phases, two MFMA k-steps per phase
+ *   10: as 7 with phases twice as long (four MFMA k-steps per phase).  Large problems use 10 for INT4
+ *      and 7 for INT8 and bf16; one workgroup per CU then walks its tiles and fetches the first stage
+ *      of the next tile before it stores the current one
  *   8: as 7 with one k-slice per phase        9: as 7 with 64-byte k-stages in a ring of 4 buffers
  *   0: as 7 with LDS reads interleaved between the MFMAs and one barrier per stage, placed before the
  *      stage's last k-slice          1: as 0 with the barrier at the end of the stage

@@ -183,46 +183,52 @@ __device__ __forceinline__ void store_tile_as(acc_t (&acc)[FM][FN], int row0, in
 // memory sees full 128-byte row segments: the wave writes its tile as [row][column] (16-byte units
 // XOR-swizzled with the row to spread banks), reads it back 16 bytes per lane, and stores 16 bytes
 // per lane with 64/UNITS complete rows per instruction.  `stage` must hold FM*32 x FN*32 x 2 bytes.
-template <int MODE, int YDT, int FM, int FN, bool hb = false, typename acc_t>
+template <int MODE, int YDT, int FM, int FN, bool hb = false, int CH = FM, typename acc_t>
 __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row0, int col0, float scale,
                                                    void* __restrict__ Y, int ldy, uint8_t* stage,
                                                    const float* __restrict__ bias = nullptr)
 {
+    // CH = 32-row blocks staged at a time: `stage` holds CH*32 rows and is reused FM/CH times (the
+    // LDS operations of one wave execute in order, so a chunk's reads precede the next chunk's writes)
     typedef typename OutVec<YDT>::type vec_t;              // 4 x 2 bytes
     constexpr int ROWB = FN * 32 * 2;                      // bytes per staged row
     constexpr int UNITS = ROWB / 16;
     constexpr int SW = (UNITS >= 8 ? 8 : UNITS) - 1;
     constexpr int ROWS_PER_INSTR = 64 / UNITS;
-    static_assert(sizeof(vec_t) == 8 && (FM * 32) % ROWS_PER_INSTR == 0, "staging layout");
+    static_assert(sizeof(vec_t) == 8 && (CH * 32) % ROWS_PER_INSTR == 0 && FM % CH == 0, "staging layout");
     const int lane = threadIdx.x & 63;
     const int frow = lane & 31, fhalf = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = i * 32 + frow;
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const v4f b4 = bias4(hb ? bias : nullptr, col0 + 4 * fhalf + j * 32 + 8 * g);
-                vec_t v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
-                const int u = g + 4 * j;
-                *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ (m & SW)) << 4) + 8 * fhalf) = v;
-            }
-    }
     uint8_t* Yb = static_cast<uint8_t*>(Y);
     const int mr = lane / UNITS, us = lane % UNITS;
 #pragma unroll
-    for (int t = 0; t < FM * 32 / ROWS_PER_INSTR; ++t) {
-        const int m = t * ROWS_PER_INSTR + mr;
-        const int u = us ^ (m & SW);
-        const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
-        *reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + m) * ldy + col0) * 2 + (u << 4)) = d;
+    for (int c = 0; c < FM / CH; ++c) {
+#pragma unroll
+        for (int ic = 0; ic < CH; ++ic) {
+            const int i = c * CH + ic;
+            const int m = ic * 32 + frow;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const v4f b4 = bias4(hb ? bias : nullptr, col0 + 4 * fhalf + j * 32 + 8 * g);
+                    vec_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
+                    const int u = g + 4 * j;
+                    *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ (m & SW)) << 4) + 8 * fhalf) = v;
+                }
+        }
+#pragma unroll
+        for (int t = 0; t < CH * 32 / ROWS_PER_INSTR; ++t) {
+            const int m = t * ROWS_PER_INSTR + mr;
+            const int u = us ^ (m & SW);
+            const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
+            *reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + c * CH * 32 + m) * ldy + col0) * 2 + (u << 4)) = d;
+        }
     }
 }
 
-template <int MODE, int FM, int FN, typename acc_t>
+template <int MODE, int FM, int FN, int CH = FM, typename acc_t>
 __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N,
                                            const float* __restrict__ s_x, const float* __restrict__ s_w,
                                            void* __restrict__ Y, int y_dtype, int ldy, uint8_t* stage = nullptr,
@@ -232,7 +238,7 @@ __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int c
                       (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
     const bool staged = fast && stage != nullptr && (ldy & 7) == 0 && (col0 & 7) == 0;
     if constexpr (MODE == MODE_BF16) {
-        if (staged) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, 1.0f, Y, ldy, stage);
+        if (staged) store_tile_via_lds<MODE, FQ_BF16, FM, FN, false, CH>(acc, row0, col0, 1.0f, Y, ldy, stage);
         else store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, 1.0f, Y, ldy, fast);
     } else {
         if (y_dtype == FQ_I32) {
@@ -242,15 +248,15 @@ __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int c
         const float scale = (*s_x) * (*s_w);
         if (bias) {
             // the biased epilogue is a separate instantiation so that the plain one carries none of it
-            if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN, true>(acc, row0, col0, scale, Y, ldy, stage, bias);
-            else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN, true>(acc, row0, col0, scale, Y, ldy, stage, bias);
+            if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN, true, CH>(acc, row0, col0, scale, Y, ldy, stage, bias);
+            else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN, true, CH>(acc, row0, col0, scale, Y, ldy, stage, bias);
             else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
             else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
             else store_tile_as<MODE, FQ_F32, FM, FN, true>(acc, row0, col0, M, N, scale, Y, ldy, fast, bias);
             return;
         }
-        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
-        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN>(acc, row0, col0, scale, Y, ldy, stage);
+        if (staged && y_dtype == FQ_BF16) store_tile_via_lds<MODE, FQ_BF16, FM, FN, false, CH>(acc, row0, col0, scale, Y, ldy, stage);
+        else if (staged && y_dtype == FQ_F16) store_tile_via_lds<MODE, FQ_F16, FM, FN, false, CH>(acc, row0, col0, scale, Y, ldy, stage);
         else if (y_dtype == FQ_BF16) store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
         else if (y_dtype == FQ_F16) store_tile_as<MODE, FQ_F16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
         else store_tile_as<MODE, FQ_F32, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
@@ -307,8 +313,12 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
                                               const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                               const float* __restrict__ s_x, const float* __restrict__ s_w,
                                               void* __restrict__ Y, int y_dtype, int ldy,
-                                              const float* __restrict__ bias)
+                                              const float* __restrict__ bias, bool prefetched = false,
+                                              bool has_next = false, int m0_next = 0, int n0_next = 0)
 {
+    // prefetched / has_next (two-buffer ping-pong pipeline only): a workgroup that walks several tiles
+    // issues the first stage of its next tile before it stores the current one, and then skips that
+    // issue when it starts the next tile.
     constexpr int NW = WM * WN;
     constexpr int CPR = BKB / 16;              // chunks per row per stage
     constexpr int RPB = 64 / CPR;              // rows of one 1 KiB DMA block (one wave instruction)
@@ -330,6 +340,9 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
     static_assert((RPB * NW) % 16 == 0, "swizzle must repeat across a wave's DMA blocks");
     static_assert(CPR == 4 || CPR == 8, "BKB must be 64 or 128");
     typedef typename Acc<MODE>::type acc_t;
+    // next-tile prefetch across the epilogue: every DMA wait of the two-buffer pipeline is vmcnt(0), so
+    // the epilogue's stores in the same counter cannot be mistaken for a landed stage
+    constexpr bool OVERLAP = PIPE == 2 && NSTAGE == 2;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -344,12 +357,15 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
     const int nk_full = rowbytes / BKB;
     const int nk = nk_full + ((rowbytes % BKB) ? 1 : 0);
     uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
+    auto set_offsets = [&](int mt, int nt) {
 #pragma unroll
-    for (int j = 0; j < A_BLOCKS; ++j)
-        offA[j] = (uint32_t)min(m0 + (wave + j * NW) * RPB + drow, M - 1) * (uint32_t)rowbytes + dchunk * 16;
+        for (int j = 0; j < A_BLOCKS; ++j)
+            offA[j] = (uint32_t)min(mt + (wave + j * NW) * RPB + drow, M - 1) * (uint32_t)rowbytes + dchunk * 16;
 #pragma unroll
-    for (int j = 0; j < B_BLOCKS; ++j)
-        offB[j] = (uint32_t)min(n0 + (wave + j * NW) * RPB + drow, N - 1) * (uint32_t)rowbytes + dchunk * 16;
+        for (int j = 0; j < B_BLOCKS; ++j)
+            offB[j] = (uint32_t)min(nt + (wave + j * NW) * RPB + drow, N - 1) * (uint32_t)rowbytes + dchunk * 16;
+    };
+    set_offsets(m0, n0);
 
     const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
     auto issue_stage = [&](int buf, int kb, auto tail_tag) {
@@ -470,16 +486,19 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
         //      With more than two buffers, NSTAGE-1 stages are in flight and the waits leave NSTAGE-2 of
         //      them outstanding (all of them once no further stage is issued).
         static_assert(PIPE != 2 || NW == 8, "ping-pong pipeline: 8 waves");
-        constexpr int SPP = (MODE == MODE_I4) ? 1 : PP_SLICES;     // packed k-slices per phase
+        // PP_SLICES = MFMA k-steps (operand sets) per phase; a packed INT4 slice yields two of them
+        constexpr int SPP = (MODE == MODE_I4) ? (PP_SLICES >= 2 ? PP_SLICES / 2 : 1) : PP_SLICES;   // LDS k-slices per phase
         constexpr int NPH = KS / SPP;
-        constexpr int NOP = (MODE == MODE_I4) ? 2 * SPP : SPP;     // operand sets (MFMA k-steps) per phase
+        constexpr int NOP = (MODE == MODE_I4) ? 2 * SPP : SPP;     // operand sets per phase
         static_assert(KS % SPP == 0, "phases must tile the stage");
         const bool group_b = wave >= 4;
         v4i pa[NOP][FM], pb[NOP][FN];
 
+        if (!(OVERLAP && prefetched)) {
 #pragma unroll
-        for (int st = 0; st < NSTAGE - 1; ++st)
-            if (st < nk) issue_any(st);
+            for (int st = 0; st < NSTAGE - 1; ++st)
+                if (st < nk) issue_any(st);
+        }
         if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
         __builtin_amdgcn_s_barrier();
@@ -502,16 +521,14 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
 #pragma unroll
                     for (int j = 0; j < FN; ++j) rb[j] = *reinterpret_cast<const v4i*>(s + b_rd + j * 32 * BKB + kofs[ks]);
                     if constexpr (MODE == MODE_I4) {
+                        // INT4: only the operands of the first MFMA are widened here; the rest is
+                        // widened in the compute phase, in the shadow of the MFMAs (see below)
 #pragma unroll
-                        for (int i = 0; i < FM; ++i) {
-                            pa[2 * q][i] = (ra[i] << 4) & (int)0xf0f0f0f0;
-                            pa[2 * q + 1][i] = ra[i] & (int)0xf0f0f0f0;
-                        }
+                        for (int i = 0; i < FM; ++i) pa[2 * q + 1][i] = ra[i];
 #pragma unroll
-                        for (int j = 0; j < FN; ++j) {
-                            pb[2 * q][j] = (rb[j] << 4) & (int)0xf0f0f0f0;
-                            pb[2 * q + 1][j] = rb[j] & (int)0xf0f0f0f0;
-                        }
+                        for (int j = 0; j < FN; ++j) pb[2 * q + 1][j] = rb[j];
+                        pa[2 * q][0] = (ra[0] << 4) & (int)0xf0f0f0f0;
+                        pb[2 * q][0] = (rb[0] << 4) & (int)0xf0f0f0f0;
                     } else {
 #pragma unroll
                         for (int i = 0; i < FM; ++i) pa[q][i] = ra[i];
@@ -529,19 +546,57 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
                 __builtin_amdgcn_sched_barrier(0);
                 // ---------------- compute phase ----------------
                 __builtin_amdgcn_s_setprio(1);
+                if constexpr (MODE == MODE_I4) {
+                    // For packed slice q, pa[2q+1] / pb[2q+1] hold the packed operands.  Low nibbles
+                    // (x << 4) & 0xf0.. go to pa[2q] / pb[2q] and feed the first FM*FN MFMAs; the high
+                    // nibbles x & 0xf0.. are formed in place for the second FM*FN.  Each widening is
+                    // issued right after an earlier MFMA, so it executes while that MFMA occupies the
+                    // matrix pipe, and at least one MFMA before its first use.
+                    constexpr int NM = FM * FN;
+                    static_assert((FN - 1) + (FM - 1) + (FM > FN ? FM : FN) <= NM, "widening must finish within the low half");
 #pragma unroll
-                for (int o = 0; o < NOP; ++o)
+                    for (int q = 0; q < SPP; ++q) {
+                        auto widen_after = [&](int t) {
+                            // after MFMA t of the low half: production order b[1..FN-1], a[1..FM-1] as the
+                            // (i, j) walk needs them, then the high halves, two operands per slot
+                            if (t < FN - 1) pb[2 * q][t + 1] = (pb[2 * q + 1][t + 1] << 4) & (int)0xf0f0f0f0;
+                            else if (t - (FN - 1) < FM - 1) {
+                                const int i = t - (FN - 1) + 1;
+                                pa[2 * q][i] = (pa[2 * q + 1][i] << 4) & (int)0xf0f0f0f0;
+                            } else {
+                                const int u = t - (FN - 1) - (FM - 1);          // 0, 1, ...
+                                if (u < FM) pa[2 * q + 1][u] = pa[2 * q + 1][u] & (int)0xf0f0f0f0;
+                                if (u < FN) pb[2 * q + 1][u] = pb[2 * q + 1][u] & (int)0xf0f0f0f0;
+                            }
+                        };
 #pragma unroll
-                    for (int i = 0; i < FM; ++i)
-#pragma unroll
-                        for (int j = 0; j < FN; ++j) {
-                            if constexpr (MODE == MODE_BF16)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, pb[o][j]),
-                                                                                   __builtin_bit_cast(v8bf, pa[o][i]),
-                                                                                   acc[i][j], 0, 0, 0);
-                            else
-                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[o][j], pa[o][i], acc[i][j], 0, 0, 0);
+                        for (int t = 0; t < NM; ++t) {
+                            const int i = t / FN, j = t % FN;
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[2 * q][j], pa[2 * q][i], acc[i][j], 0, 0, 0);
+                            widen_after(t);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
+#pragma unroll
+                        for (int t = 0; t < NM; ++t) {
+                            const int i = t / FN, j = t % FN;
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[2 * q + 1][j], pa[2 * q + 1][i], acc[i][j], 0, 0, 0);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int o = 0; o < NOP; ++o)
+#pragma unroll
+                        for (int i = 0; i < FM; ++i)
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                if constexpr (MODE == MODE_BF16)
+                                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, pb[o][j]),
+                                                                                       __builtin_bit_cast(v8bf, pa[o][i]),
+                                                                                       acc[i][j], 0, 0, 0);
+                                else
+                                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pb[o][j], pa[o][i], acc[i][j], 0, 0, 0);
+                            }
+                }
                 __builtin_amdgcn_s_setprio(0);
                 if (ph == NPH - 1 && !group_b) {                                    // A: my DMA of stage kt+1 landed
                     if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
@@ -553,6 +608,13 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
             }
         }
         if (!group_b) __builtin_amdgcn_s_barrier();
+        // Every wave is past its last LDS operand read and has waited for all of its DMA: buffer 0 may
+        // receive the next tile's first stage while this tile is stored from registers through the
+        // other buffer.
+        if (OVERLAP && has_next) {
+            set_offsets(m0_next, n0_next);
+            issue_any(0);
+        }
     } else if constexpr (PIPE == 0) {
         // ---- end-of-stage barrier, NSTAGE buffers: NSTAGE-1 stages in flight ----
 #pragma unroll
@@ -608,9 +670,20 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
 
     // After the last barrier of the loop no wave reads the stage buffers any more (the operands of
     // the final k-slice are in registers), so each wave may reuse its share of LDS to stage its output.
-    constexpr bool CAN_STAGE = NW * TM * TN * 2 <= NSTAGE * STAGE;
-    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
-                             CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr, bias);
+    if constexpr (OVERLAP) {
+        // buffer 0 may be filling with the next tile's first stage: stage the output through this
+        // wave's share of buffer 1, as many 32-row blocks at a time as fit
+        constexpr int SHARE = STAGE / NW;
+        constexpr int CH_FIT = SHARE / (32 * TN * 2);
+        constexpr int CH = CH_FIT >= FM ? FM : (CH_FIT >= 2 ? 2 : CH_FIT);
+        static_assert(CH >= 1 && FM % CH == 0, "output staging must fit the wave's share of a stage buffer");
+        store_tile<MODE, FM, FN, CH>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                                     smem + STAGE + wave * SHARE, bias);
+    } else {
+        constexpr bool CAN_STAGE = NW * TM * TN * 2 <= NSTAGE * STAGE;
+        store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                                 CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr, bias);
+    }
 }
 
 // The kernel.  Workgroups [0, n_main) compute full BM x BN tiles.  When the number of tiles leaves a
@@ -623,27 +696,42 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
                                                                 int rowbytes, const float* __restrict__ s_x,
                                                                 const float* __restrict__ s_w,
                                                                 void* __restrict__ Y, int y_dtype, int ldy,
-                                                                int tiles_m, int tiles_n, int n_main, Batch bt)
+                                                                int tiles_m, int tiles_n, int n_main, int n_tail, Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     // batched launches: blockIdx.y selects the problem
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
     Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
-    const int wg = blockIdx.x;
+    // Workgroup w walks the virtual workgroup ids w, w + gridDim.x, ...: ids below n_main are full
+    // tiles, the rest half tiles.  (With gridDim.x >= n_main + 2 n_tail each workgroup has one id.)
+    constexpr bool CAN_PREFETCH = PIPE == 2 && NSTAGE == 2;     // see gemm_dma_tile
+    const int n_ids = n_main + 2 * n_tail;
     int tile_m, tile_n;
-    if (wg < n_main) {
-        tile_of_workgroup(wg, n_main, tiles_m, tiles_n, tile_m, tile_n);
-        gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
-                                                                s_x, s_w, Y, y_dtype, ldy, bt.bias);
-    } else {
-        if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
-            const int t = wg - n_main;
-            tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
-            gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM + (t & 1) * (BM / 2),
-                                                                        tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
-                                                                        Y, y_dtype, ldy, bt.bias);
+    bool prefetched = false;
+    for (int v = blockIdx.x; v < n_ids; v += gridDim.x) {
+        if (v < n_main) {
+            tile_of_workgroup(v, n_main, tiles_m, tiles_n, tile_m, tile_n);
+            const int vn = v + gridDim.x;
+            const bool has_next = vn < n_main;
+            int next_m = 0, next_n = 0;
+            if (has_next) tile_of_workgroup(vn, n_main, tiles_m, tiles_n, next_m, next_n);
+            gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
+                                                                    s_x, s_w, Y, y_dtype, ldy, bt.bias, prefetched,
+                                                                    has_next, next_m * BM, next_n * BN);
+            prefetched = CAN_PREFETCH && has_next;
+        } else {
+            if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
+                const int t = v - n_main;
+                tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
+                gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM + (t & 1) * (BM / 2),
+                                                                            tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
+                                                                            Y, y_dtype, ldy, bt.bias);
+            }
         }
+        // the stage buffers are reused by the next tile: every wave must be done staging its output
+        // (a tile that was prefetched synchronizes on its own first barrier instead, after its waits)
+        if (v + (int)gridDim.x < n_ids && !prefetched) __syncthreads();
     }
 }
 
@@ -804,9 +892,14 @@ int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const f
         n_tail = r;
         n_main = (int)tiles - r;
     }
-    kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(WM * WN * 64), smem, stream>>>(
+    // The two-buffer ping-pong kernel runs one workgroup per CU that walks its tiles in rounds and
+    // prefetches across tile boundaries; the others get one workgroup per tile.
+    constexpr bool PERSISTENT = PIPE == 2 && NSTAGE == 2;
+    int grid_x = n_main + 2 * n_tail;
+    if (PERSISTENT && bt.count == 1 && grid_x > cus) grid_x = cus;
+    kern<<<dim3((unsigned)grid_x, (unsigned)bt.count), dim3(WM * WN * 64), smem, stream>>>(
         static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
-        tiles_m, tiles_n, n_main, bt);
+        tiles_m, tiles_n, n_main, n_tail, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;
@@ -841,7 +934,9 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
         // short reductions (a few k-tiles) leave the output write as the bound: the smaller tile runs
         // two workgroups per CU so that one's epilogue overlaps the other's loads
-        v = (big_tiles >= 192 && rowbytes > 512 && N > 128) ? 7 : 6;
+        // long phases (10) where the operand registers allow it: INT8 and bf16 would hold four unpacked
+        // k-slices per phase and spill, so they keep two k-slices per phase (7)
+        v = (big_tiles >= 192 && rowbytes > 512 && N > 128) ? (MODE == MODE_I4 ? 10 : 7) : 6;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
@@ -854,6 +949,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 10: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }

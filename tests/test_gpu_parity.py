@@ -155,7 +155,7 @@ def _gemm_acc(Xq, Wq, bits):
     return Y.cpu().numpy()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_gemm_accumulators_bit_exact(variant, bits):
     rng = np.random.default_rng(100 * variant + bits)
@@ -339,7 +339,7 @@ def test_bmm_accumulators_bit_exact(batch, M, N, Kpad, bits):
     np.testing.assert_array_equal(Y.cpu().numpy(), ref)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 5, 6, 7])
+@pytest.mark.parametrize("variant", [0, 2, 5, 6, 7, 10])
 def test_bmm_variants_and_padded_strides(variant):
     """Every kernel family with batch strides larger than one matrix (operands and output live in
     wider buffers; the gaps must stay untouched) and a 2-byte dequantized output."""
@@ -451,7 +451,7 @@ def test_two_sided_flatten_end_to_end(bits):
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("ydt", ["f32", "bf16", "f16"])
-@pytest.mark.parametrize("variant", [-1, 7, 2])
+@pytest.mark.parametrize("variant", [-1, 10, 2])
 def test_linear_bias(bits, ydt, variant):
     """fq_linear_bias: y = acc * s_x * s_w + bias[n].  Tolerance: the product and the sum are each rounded
     to fp32 (2^-24 of |product| and of |y|), then the output type's half ulp of |y|; measured against
