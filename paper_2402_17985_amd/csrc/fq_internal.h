@@ -25,11 +25,13 @@ inline int elem_size(int dtype)
     }
 }
 
-// Workspace layout of the activation path: [cmax: K u32][mslot: Kpad f32][scalars: 4 f32]
+// Workspace layout of the activation path: [cmax: K u32][mslot: Kpad f32][scalars: 4 f32][gflag: Kpad/16 u8]
 struct ActWorkspace {
     uint32_t* cmax;   // per input channel max|x| as fp32 bit patterns
     float* mslot;     // per flattened slot multiplier m_p
     float* scalars;   // [0] = a'
+    uint8_t* gflag;   // per group of 16 slots: 1 = the 16 channels at the same indices; then, Kpad/16 + 1
+                      // bytes further, cflag: 1 = every slot repeats an identity slot's value or holds 0
     size_t bytes;
 };
 ActWorkspace carve_act_workspace(void* base, int K, int Kpad);

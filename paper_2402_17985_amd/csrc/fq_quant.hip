@@ -190,7 +190,7 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
                                                      const int32_t* __restrict__ rep, int Kpad, int qmax,
                                                      int mode, const float* __restrict__ absmax_in, float T,
                                                      float* __restrict__ mslot, float* __restrict__ scale_out,
-                                                     float* __restrict__ scalars)
+                                                     float* __restrict__ scalars, uint8_t* __restrict__ gflag)
 {
     // Peel split (modes 3 dynamic / 4 static): `rep` carries the slot ordinals e; mslot[p] receives the
     // offset fl32(e * T) that the slot subtracts from |x| (+inf in padding, which clamps to 0), and the
@@ -277,6 +277,24 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
         if (valid) m = (n < 1024) ? table[n] : (float)((double)qmax / ((double)n * ad));
         mslot[p] = m;
     }
+    // gflag[g] = 1 when the 16 slots of group g are the 16 channels at the same indices (the head of
+    // the map): such a group is read with vector loads and its quantized values can be copied by the
+    // appended slots that repeat its channels
+    const bool ident = p < Kpad && p < K && src[p] == p;
+    const unsigned long long bal = __ballot(ident);
+    if (p < Kpad && (tid & 15) == 0) gflag[p >> 4] = (((bal >> (tid & 48)) & 0xffffull) == 0xffffull) ? 1 : 0;
+    // cflag[g] = 1 when every slot of group g either holds 0 whatever the input (padding) or repeats a
+    // channel j < 16 * (K / 16) whose own slot j is the identity slot with the same copy count: the
+    // slot's quantized value then equals slot j's and can be copied instead of recomputed
+    bool copyable = false;
+    if (p < Kpad) {
+        const int j = src[p];
+        if ((unsigned)j >= (unsigned)K) copyable = true;
+        else if (j < ((K >> 4) << 4) && src[j] == j) copyable = (mode == 2) || (rep[p] > 0 && rep[j] == rep[p]);
+    }
+    const unsigned long long balc = __ballot(copyable);
+    uint8_t* cflag = gflag + ((Kpad >> 4) + 1);
+    if (p < Kpad && (tid & 15) == 0) cflag[p >> 4] = (((balc >> (tid & 48)) & 0xffffull) == 0xffffull) ? 1 : 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -392,6 +410,157 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// flatten + quantize, row-strip form (the equal split)
+// ---------------------------------------------------------------------------------------------
+// A workgroup owns a strip of R rows.  Phase 1: each thread takes groups among the first K/16 (the
+// head of the map): a group whose 16 slots are the 16 channels at the same indices (gflag) is read
+// with vector loads, otherwise gathered; multiply, round, clamp, pack, store, and the quantized value
+// of every identity slot also goes to LDS as a byte, q[row][channel].  Phase 2: the remaining groups
+// (appended copies and padding), one (group, row) item at a time over all threads.  An appended slot
+// with the same copy count as its channel's identity slot holds the same quantized value, so a group
+// made of such slots and padding (cflag) is copied from LDS; any other group is gathered from global
+// memory and quantized with its own multipliers.
+template <int DT, int BITS>
+__global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __restrict__ Xv, int M, int K, int ld,
+                                                                 const int32_t* __restrict__ src,
+                                                                 const float* __restrict__ mslot,
+                                                                 const uint8_t* __restrict__ gflag, int Kpad, int R,
+                                                                 uint8_t* __restrict__ out)
+{
+    typedef typename Elem<DT>::type T;
+    constexpr int VEC = Elem<DT>::VEC;
+    extern __shared__ __align__(16) uint8_t lds[];
+    const T* X = static_cast<const T*>(Xv);
+    const int NH = K >> 4;                                     // groups of the head
+    const int KQ = NH << 4;
+    const int G = Kpad >> 4;
+    const int NT = G - NH;                                     // groups of phase 2
+    uint8_t* qs = lds;                                         // [R][KQ] int8
+    uint16_t* ts = reinterpret_cast<uint16_t*>(lds + (size_t)R * KQ);   // sources of the phase-2 slots
+    const uint8_t* cflag = gflag + (G + 1);
+    const int r0 = blockIdx.x * R;
+    const int nr = min(M - r0, R);
+    const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
+
+    // sources of the phase-2 slots as 16-bit channel numbers (0xffff: the slot holds 0)
+    for (int t = threadIdx.x; t < NT * 16; t += 256) {
+        const int j = src[KQ + t];
+        ts[t] = ((unsigned)j < (unsigned)KQ) ? (uint16_t)j : (uint16_t)0xffff;
+    }
+
+    auto pack_store = [&](const int (&q)[16], uint8_t* o) {
+        if (BITS == 8) {
+            v4u w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
+                       ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
+            *reinterpret_cast<v4u*>(o) = w;
+        } else {
+            v2u w;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint32_t acc = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc |= (uint32_t)(q[8 * i + j] & 0xf) << (4 * j);
+                w[i] = acc;
+            }
+            *reinterpret_cast<v2u*>(o) = w;
+        }
+    };
+    // the general form of one group over rows [ra, rb) of the strip: every slot's source element is
+    // gathered from global memory; identity slots of the head also leave their value in LDS
+    auto gather_group = [&](int g, int ra, int rb, bool to_lds) {
+        const int p0 = g << 4;
+        int s[16];
+        float m[16];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v4i sv = *reinterpret_cast<const v4i*>(src + p0 + 4 * i);
+            v4f mv = *reinterpret_cast<const v4f*>(mslot + p0 + 4 * i);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { s[4 * i + j] = sv[j]; m[4 * i + j] = mv[j]; }
+        }
+        bool ident[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            ident[i] = to_lds && s[i] == p0 + i;
+            if ((unsigned)s[i] >= (unsigned)K) { s[i] = 0; m[i] = 0.0f; }
+        }
+        uint8_t* o = out + (size_t)(r0 + ra) * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
+        const T* row = X + (size_t)(r0 + ra) * ld;
+        for (int r = ra; r < rb; ++r, row += ld, o += orow_bytes) {
+            int q[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(Elem<DT>::widen(row[s[i]]), m[i]);
+            pack_store(q, o);
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (ident[i]) qs[(size_t)r * KQ + p0 + i] = (uint8_t)q[i];
+        }
+    };
+
+    // ---- phase 1: the head ----
+    for (int g = threadIdx.x; g < NH; g += 256) {
+        if (!gflag[g]) {
+            gather_group(g, 0, nr, true);
+            continue;
+        }
+        const int p0 = g << 4;
+        float m[16];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v4f mv = *reinterpret_cast<const v4f*>(mslot + p0 + 4 * i);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) m[4 * i + j] = mv[j];
+        }
+        uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
+        const T* row = X + (size_t)r0 * ld + p0;
+        uint8_t* ql = qs + p0;
+#pragma unroll 4
+        for (int r = 0; r < nr; ++r, row += ld, o += orow_bytes, ql += KQ) {
+            float x[16];
+            const v4u* vp = reinterpret_cast<const v4u*>(row);
+#pragma unroll
+            for (int i = 0; i < 16 / VEC; ++i) widen16<DT>(vp[i], x + i * VEC);
+            int q[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(x[i], m[i]);
+            pack_store(q, o);
+            v4u w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
+                       ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
+            *reinterpret_cast<v4u*>(ql) = w;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: appended copies and padding, (group, row) items over all threads ----
+    for (int it = threadIdx.x; it < NT * nr; it += 256) {
+        const int gt = it % NT, r = it / NT;
+        const int g = NH + gt;
+        if (!cflag[g]) {
+            gather_group(g, r, r + 1, false);
+            continue;
+        }
+        const v4u* tp = reinterpret_cast<const v4u*>(ts + gt * 16);
+        const v4u t0 = tp[0], t1 = tp[1];
+        const int8_t* ql = reinterpret_cast<const int8_t*>(qs) + (size_t)r * KQ;
+        int q[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t word = (i < 8) ? t0[i >> 1] : t1[(i - 8) >> 1];
+            const uint32_t j = (i & 1) ? (word >> 16) : (word & 0xffffu);
+            q[i] = (j == 0xffffu) ? 0 : (int)ql[j];
+        }
+        pack_store(q, out + (size_t)(r0 + r) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3)));
+    }
+}
+
 // Per input channel max|x| into cmax (fp32 bit patterns, which order like the non-negative floats
 // they hold); accumulate keeps what cmax holds on entry as the starting value.
 template <int DT>
@@ -401,7 +570,7 @@ void launch_colabsmax(const void* X, int M, int K, int ld, bool accumulate, uint
     if (!accumulate) fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(cmax, K, 0u);
     const int bx = (K + 64 * VEC - 1) / (64 * VEC);
     // a workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves); aim at
-    // about 1024 workgroups, at most 512 rows each
+    // about 1024 workgroups, at most 512 rows each (more, smaller workgroups measured slower)
     long long rpb = ((long long)M * bx + 1023) / 1024;
     rpb = (rpb + 63) / 64 * 64;
     if (rpb < 128) rpb = 128;
@@ -419,14 +588,32 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     const bool peel = mode >= 3;
     if (mode != 1 && mode != 4) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, T,
-                                                            ws.mslot, scale_out, ws.scalars);
+                                                            ws.mslot, scale_out, ws.scalars, ws.gflag);
+    uint8_t* o8 = static_cast<uint8_t*>(out);
+    if (!peel && K >= 16) {
+        // row-strip kernel: R rows per workgroup with R * K bytes of LDS plus 2 bytes per appended slot
+        // (at most 64 KiB, so that two workgroups fit a CU); wider layers use the general kernel below
+        const size_t kq = (size_t)(K & ~15), tail_src = 2 * ((size_t)Kpad - kq);
+        int R = 8;
+        while (R > 1 && (size_t)R * kq + tail_src > 64u * 1024u) R >>= 1;
+        const size_t lds = (size_t)R * kq + tail_src;
+        if (lds <= 64u * 1024u) {
+            const unsigned nblk = (unsigned)((M + R - 1) / R);
+            if (bits == 8)
+                flatten_quant_rows_kernel<DT, 8><<<nblk, 256, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+            else
+                flatten_quant_rows_kernel<DT, 4><<<nblk, 256, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return fail(FQ_ERR_HIP, "flatten-quantize launch failed: %s", hipGetErrorString(e));
+            return FQ_OK;
+        }
+    }
     const int G = Kpad / 16;
     // rows per thread: as many as 8 while the launch still has >= 2048 waves
     int rpt = 8;
     while (rpt > 1 && ((long long)G * ((M + rpt - 1) / rpt)) < 2048LL * 64) rpt >>= 1;
     const long long threads = (long long)G * ((M + rpt - 1) / rpt);
     const unsigned blocks = (unsigned)((threads + 255) / 256);
-    uint8_t* o8 = static_cast<uint8_t*>(out);
     if (peel && bits == 8)
         flatten_quant_kernel<DT, 8, true><<<blocks, 256, 0, stream>>>(X, M, K, ld, src_idx, ws.mslot, Kpad, rpt, o8, ws.scalars, T);
     else if (peel)
@@ -453,6 +640,8 @@ ActWorkspace carve_act_workspace(void* base, int K, int Kpad)
     off += round_up((size_t)Kpad * 4, 256);
     ws.scalars = reinterpret_cast<float*>(p + off);
     off += 256;
+    ws.gflag = p + off;
+    off += round_up(2 * (size_t)(Kpad / 16 + 1), 256);       // gflag, then cflag
     ws.bytes = off;
     return ws;
 }
