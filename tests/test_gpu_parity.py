@@ -490,3 +490,44 @@ def test_linear_bias(bits, ydt, variant):
     fq.fq_linear(X, lay.src, lay.rep, lay.Wq, lay.s_w, bits, Y1, ws)
     torch.cuda.synchronize()
     assert torch.equal(Y0, Y1)
+
+
+# ------------------------------------------------------------------------------------------
+# maps that do not come from the plan functions (the kernel's general paths)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("static", [False, True])
+def test_flatten_quant_act_irregular_map(bits, static):
+    """Any (src_idx, rep) is a valid map: head groups that are not the identity, appended slots whose
+    copy count differs from their channel's, sources beyond the last full group of 16, padding in the
+    middle.  The fast paths must not be taken for these, and the result still equals the definition."""
+    rng = np.random.default_rng(42 + bits)
+    M, K, Kpad = 77, 200, 512                                  # K % 16 = 8: channels 192..199 have no full head group
+    X = (rng.standard_normal((M, K)) * rng.choice([1, 1, 10], K)).astype(np.float32)
+    src = np.full(Kpad, -1, dtype=np.int32)
+    rep = np.zeros(Kpad, dtype=np.int32)
+    src[:K] = np.arange(K)
+    rep[:K] = rng.integers(1, 4, K)
+    src[16:32] = src[16:32][::-1]                               # a head group that is a permutation
+    src[40] = 7                                                 # a head slot pointing elsewhere
+    rep[40] = rep[7]
+    tail = np.arange(K + 8, 420)
+    src[tail] = rng.integers(0, K, tail.size)
+    rep[tail] = rep[src[tail]]
+    odd = tail[::5]
+    rep[odd] = rep[src[odd]] + 1                                # copy count differs from the channel's own slot
+    src[300:316] = -1                                           # a padding group in the middle
+    rep[300:316] = 0
+    src[330:346] = 199                                          # a source outside the full head groups
+    rep[330:346] = rep[199]
+    a_ref = np.float32(3.0) if static else O.act_absmax_dynamic(X, src, rep)
+    q_ref, s_ref = O.flatten_quant_act(X, src, rep, bits, a_ref)
+    want = q_ref.view(np.uint8) if bits == 8 else O.pack_i4(q_ref)
+    out = torch.full((M, Kpad if bits == 8 else Kpad // 2), 0x55, dtype=torch.uint8, device=DEV)
+    s_x = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = bytes_ws(fq.fq_act_workspace_bytes(K, Kpad))
+    fq.fq_flatten_quant_act(torch.from_numpy(X).to(DEV), dev_i32(src), dev_i32(rep), bits, out, s_x, ws,
+                            absmax_in=scalar(3.0) if static else None)
+    torch.cuda.synchronize()
+    assert np.float32(s_x.item()) == s_ref
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
