@@ -223,7 +223,10 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
             const int m = t * ROWS_PER_INSTR + mr;
             const int u = us ^ (m & SW);
             const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
-            *reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + c * CH * 32 + m) * ldy + col0) * 2 + (u << 4)) = d;
+            // the output is written once and not read by this kernel: a streaming store of whole 128-byte
+            // lines keeps it from displacing the operand panels in L2 (partial-line streaming stores, as
+            // the unstaged path would issue, are several times slower than ordinary ones)
+            __builtin_nontemporal_store(d, reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + c * CH * 32 + m) * ldy + col0) * 2 + (u << 4)));
         }
     }
 }
@@ -932,11 +935,10 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     int v = forced_gemm_variant();
     if (v < 0) {
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
-        // short reductions (a few k-tiles) leave the output write as the bound: the smaller tile runs
-        // two workgroups per CU so that one's epilogue overlaps the other's loads
+        // narrow outputs (N <= 128, the P V product of attention) and small problems use the 128x128 tile
         // long phases (10) where the operand registers allow it: INT8 and bf16 would hold four unpacked
         // k-slices per phase and spill, so they keep two k-slices per phase (7)
-        v = (big_tiles >= 192 && rowbytes > 512 && N > 128) ? (MODE == MODE_I4 ? 10 : 7) : 6;
+        v = (big_tiles >= 192 && N > 128) ? (MODE == MODE_I4 ? 10 : 7) : 6;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
