@@ -202,6 +202,7 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
         float a;
         if (mode == 3) {
             float best = 0.0f;
+#pragma unroll 8
             for (int j = tid; j < K; j += 1024) best = fmaxf(best, __uint_as_float(cmax[j]));
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off, 64));
@@ -239,11 +240,28 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
     if (mode != 1) {
         Quot best = {0.0f, 1};
         if (mode == 0) {
-            for (int p = tid; p < Kpad; p += 1024) {
-                const int s = src[p], n = rep[p];
-                if ((unsigned)s < (unsigned)K && n > 0) best = quot_max(best, Quot{__uint_as_float(cmax[s]), n});
+            // eight slots per thread at a time: all map loads, then all gathers of the channel maxima, so
+            // that a pass costs two memory latencies instead of two per slot
+            for (int base = tid; base < Kpad; base += 8 * 1024) {
+                int s[8], n[8];
+                float c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int p = base + u * 1024;
+                    s[u] = (p < Kpad) ? src[p] : -1;
+                    n[u] = (p < Kpad) ? rep[p] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool ok = (unsigned)s[u] < (unsigned)K && n[u] > 0;
+                    c[u] = ok ? __uint_as_float(cmax[s[u]]) : 0.0f;
+                    if (!ok) n[u] = 1;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) best = quot_max(best, Quot{c[u], n[u]});
             }
         } else {
+#pragma unroll 8
             for (int j = tid; j < K; j += 1024) best = quot_max(best, Quot{__uint_as_float(cmax[j]), 1});
         }
         best = wave_quot_max(best);
