@@ -531,3 +531,41 @@ def test_flatten_quant_act_irregular_map(bits, static):
     torch.cuda.synchronize()
     assert np.float32(s_x.item()) == s_ref
     np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------------------------------
+# the calls are capturable: no allocation, no synchronization, clears done by fill kernels
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [8, 4])
+def test_linear_replayed_from_a_graph(bits):
+    """fq_linear captured once into a HIP graph and replayed with new inputs between replays: every
+    replay equals the eager call on the same input (raw accumulators, so the comparison is exact)."""
+    L = _layer("cfg3", M_override=300, K_override=1024, N_override=264)
+    M, K = L.X.shape
+    N = L.W.shape[0]
+    lay = fq.FqLinear(to_dev(L.W_store, L.spec.w_dtype), L.chmax, L.T, bits, device=DEV)
+    ws = bytes_ws(fq.fq_linear_workspace_bytes(M, K, lay.Kpad, bits))
+    X = to_dev(L.X_store, L.spec.x_dtype).clone()
+    Yg = torch.zeros((M, N), dtype=torch.int32, device=DEV)
+    Ye = torch.zeros((M, N), dtype=torch.int32, device=DEV)
+    fq.fq_linear(X, lay.src, lay.rep, lay.Wq, lay.s_w, bits, Yg, ws)      # first use outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fq.fq_linear(X, lay.src, lay.rep, lay.Wq, lay.s_w, bits, Yg, ws)
+    ws_e = bytes_ws(fq.fq_linear_workspace_bytes(M, K, lay.Kpad, bits))
+    rng = np.random.default_rng(5)
+    for rnd in range(4):
+        scale = float(rng.uniform(0.3, 1.5))
+        X.copy_((to_dev(L.X_store, L.spec.x_dtype).float() * scale).to(X.dtype))   # new contents, same buffer
+        Yg.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        fq.fq_linear(X, lay.src, lay.rep, lay.Wq, lay.s_w, bits, Ye, ws_e)
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, Ye), f"replay {rnd} differs from the eager call"
+    # and the eager result is the oracle's on the last input
+    Xh = X.float().cpu().numpy()
+    Wq_ref, s_w_ref = O.flatten_weights(L.W, lay.src_host, bits)
+    acc_ref, _, _ = O.linear(Xh, lay.src_host, lay.rep_host, Wq_ref, s_w_ref, bits, want_y=False)
+    np.testing.assert_array_equal(Ye.cpu().numpy(), acc_ref)
