@@ -96,3 +96,10 @@ def test_cfg4_opt13b_layers_full_size(idx):
 def test_cfg5_llama65b_layers_full_size(idx):
     """LLaMA-65B-scale layer, M = 16384: attention projections INT8, FFN INT4."""
     _check_layer("cfg5", idx, n_sample_rows=16, freivalds=1)
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_paper_table5_shape_full_size(idx):
+    """The shape of the paper's operator measurement (Table 5): 8 x 2048 tokens, 4096 -> 4096, about 1024
+    expanded channels; INT8 and INT4."""
+    _check_layer("cfgP", idx, n_sample_rows=24, freivalds=1)
