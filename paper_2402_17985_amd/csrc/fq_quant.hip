@@ -311,8 +311,17 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
         else if (j < ((K >> 4) << 4) && src[j] == j) copyable = (mode == 2) || (rep[p] > 0 && rep[j] == rep[p]);
     }
     const unsigned long long balc = __ballot(copyable);
+    // ... and 2 when, in addition, all 16 slots repeat the same channel (the long runs of a large
+    // outlier's copies): one value then fills the group
+    const int sp = (p < Kpad) ? src[p] : -1;
+    const int s0 = __shfl(sp, (tid & 63) & ~15, 64);
+    const unsigned long long balu = __ballot(sp == s0 && (unsigned)sp < (unsigned)K);
     uint8_t* cflag = gflag + ((Kpad >> 4) + 1);
-    if (p < Kpad && (tid & 15) == 0) cflag[p >> 4] = (((balc >> (tid & 48)) & 0xffffull) == 0xffffull) ? 1 : 0;
+    if (p < Kpad && (tid & 15) == 0) {
+        const bool all_copy = ((balc >> (tid & 48)) & 0xffffull) == 0xffffull;
+        const bool all_same = ((balu >> (tid & 48)) & 0xffffull) == 0xffffull;
+        cflag[p >> 4] = all_copy ? (all_same ? 2 : 1) : 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -438,8 +447,9 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
 // of every identity slot also goes to LDS as a byte, q[row][channel].  Phase 2: the remaining groups
 // (appended copies and padding), one (group, row) item at a time over all threads.  An appended slot
 // with the same copy count as its channel's identity slot holds the same quantized value, so a group
-// made of such slots and padding (cflag) is copied from LDS; any other group is gathered from global
-// memory and quantized with its own multipliers.
+// made of such slots and padding (cflag) is copied from LDS (one value replicated when all 16 repeat
+// the same channel, cflag = 2); any other group is gathered from global memory and quantized with its
+// own multipliers.
 template <int DT, int BITS>
 __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __restrict__ Xv, int M, int K, int ld,
                                                                  const int32_t* __restrict__ src,
@@ -457,16 +467,19 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     const int NT = G - NH;                                     // groups of phase 2
     uint8_t* qs = lds;                                         // [R][KQ] int8
     uint16_t* ts = reinterpret_cast<uint16_t*>(lds + (size_t)R * KQ);   // sources of the phase-2 slots
+    uint8_t* tf = lds + (size_t)R * KQ + (size_t)NT * 32;               // copy flags of the phase-2 groups
     const uint8_t* cflag = gflag + (G + 1);
     const int r0 = blockIdx.x * R;
+    const int nthr = blockDim.x;
     const int nr = min(M - r0, R);
     const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
 
     // sources of the phase-2 slots as 16-bit channel numbers (0xffff: the slot holds 0)
-    for (int t = threadIdx.x; t < NT * 16; t += 256) {
+    for (int t = threadIdx.x; t < NT * 16; t += nthr) {
         const int j = src[KQ + t];
         ts[t] = ((unsigned)j < (unsigned)KQ) ? (uint16_t)j : (uint16_t)0xffff;
     }
+    for (int t = threadIdx.x; t < NT; t += nthr) tf[t] = cflag[NH + t];
 
     auto pack_store = [&](const int (&q)[16], uint8_t* o) {
         if (BITS == 8) {
@@ -521,7 +534,7 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     };
 
     // ---- phase 1: the head ----
-    for (int g = threadIdx.x; g < NH; g += 256) {
+    for (int g = threadIdx.x; g < NH; g += nthr) {
         if (!gflag[g]) {
             gather_group(g, 0, nr, true);
             continue;
@@ -558,11 +571,25 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     __syncthreads();
 
     // ---- phase 2: appended copies and padding, (group, row) items over all threads ----
-    for (int it = threadIdx.x; it < NT * nr; it += 256) {
+    for (int it = threadIdx.x; it < NT * nr; it += nthr) {
         const int gt = it % NT, r = it / NT;
         const int g = NH + gt;
-        if (!cflag[g]) {
+        const uint8_t cf = tf[gt];
+        if (!cf) {
             gather_group(g, r, r + 1, false);
+            continue;
+        }
+        uint8_t* o = out + (size_t)(r0 + r) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3));
+        if (cf == 2) {
+            // all 16 slots repeat one channel: replicate its value
+            const uint32_t q1 = (uint32_t)(qs[(size_t)r * KQ + ts[gt * 16]]);
+            if (BITS == 8) {
+                const uint32_t w = q1 * 0x01010101u;
+                *reinterpret_cast<v4u*>(o) = v4u{w, w, w, w};
+            } else {
+                const uint32_t w = (q1 & 0xfu) * 0x11111111u;
+                *reinterpret_cast<v2u*>(o) = v2u{w, w};
+            }
             continue;
         }
         const v4u* tp = reinterpret_cast<const v4u*>(ts + gt * 16);
@@ -575,7 +602,7 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
             const uint32_t j = (i & 1) ? (word >> 16) : (word & 0xffffu);
             q[i] = (j == 0xffffu) ? 0 : (int)ql[j];
         }
-        pack_store(q, out + (size_t)(r0 + r) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3)));
+        pack_store(q, o);
     }
 }
 
@@ -611,16 +638,19 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     if (!peel && K >= 16) {
         // row-strip kernel: R rows per workgroup with R * K bytes of LDS plus 2 bytes per appended slot
         // (at most 64 KiB, so that two workgroups fit a CU); wider layers use the general kernel below
-        const size_t kq = (size_t)(K & ~15), tail_src = 2 * ((size_t)Kpad - kq);
+        // per appended slot 2 bytes (its source) and per appended group 1 byte (its flag)
+        const size_t kq = (size_t)(K & ~15), tail_src = 2 * ((size_t)Kpad - kq) + ((size_t)Kpad - kq) / 16;
         int R = 8;
         while (R > 1 && (size_t)R * kq + tail_src > 64u * 1024u) R >>= 1;
         const size_t lds = (size_t)R * kq + tail_src;
         if (lds <= 64u * 1024u) {
             const unsigned nblk = (unsigned)((M + R - 1) / R);
+            // 256 threads walk the strip's groups (larger workgroups, one thread per head group, measured slower)
+            const int nthr = 256;
             if (bits == 8)
-                flatten_quant_rows_kernel<DT, 8><<<nblk, 256, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+                flatten_quant_rows_kernel<DT, 8><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
             else
-                flatten_quant_rows_kernel<DT, 4><<<nblk, 256, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+                flatten_quant_rows_kernel<DT, 4><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return fail(FQ_ERR_HIP, "flatten-quantize launch failed: %s", hipGetErrorString(e));
             return FQ_OK;
