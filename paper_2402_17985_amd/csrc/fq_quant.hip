@@ -447,9 +447,8 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
 // of every identity slot also goes to LDS as a byte, q[row][channel].  Phase 2: the remaining groups
 // (appended copies and padding), one (group, row) item at a time over all threads.  An appended slot
 // with the same copy count as its channel's identity slot holds the same quantized value, so a group
-// made of such slots and padding (cflag) is copied from LDS (one value replicated when all 16 repeat
-// the same channel, cflag = 2); any other group is gathered from global memory and quantized with its
-// own multipliers.
+// made of such slots and padding (cflag) is copied from LDS; any other group is gathered from global
+// memory and quantized with its own multipliers.
 template <int DT, int BITS>
 __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __restrict__ Xv, int M, int K, int ld,
                                                                  const int32_t* __restrict__ src,
@@ -474,10 +473,20 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     const int nr = min(M - r0, R);
     const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
 
-    // sources of the phase-2 slots as 16-bit channel numbers (0xffff: the slot holds 0)
-    for (int t = threadIdx.x; t < NT * 16; t += nthr) {
-        const int j = src[KQ + t];
-        ts[t] = ((unsigned)j < (unsigned)KQ) ? (uint16_t)j : (uint16_t)0xffff;
+    // sources of the phase-2 slots as 16-bit channel numbers (0xffff: the slot holds 0); eight slots per
+    // thread and pass, loaded before any is stored, so that the passes do not each wait a round trip
+    for (int t = threadIdx.x * 8; t < NT * 16; t += nthr * 8) {
+        const v4i a = *reinterpret_cast<const v4i*>(src + KQ + t);
+        const v4i b = *reinterpret_cast<const v4i*>(src + KQ + t + 4);
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j0 = (i < 2) ? a[2 * i] : b[2 * i - 4], j1 = (i < 2) ? a[2 * i + 1] : b[2 * i - 3];
+            const uint32_t lo = ((unsigned)j0 < (unsigned)KQ) ? (uint32_t)j0 : 0xffffu;
+            const uint32_t hi = ((unsigned)j1 < (unsigned)KQ) ? (uint32_t)j1 : 0xffffu;
+            w[i] = lo | (hi << 16);
+        }
+        *reinterpret_cast<v4u*>(ts + t) = v4u{w[0], w[1], w[2], w[3]};
     }
     for (int t = threadIdx.x; t < NT; t += nthr) tf[t] = cflag[NH + t];
 
@@ -570,39 +579,47 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     }
     __syncthreads();
 
-    // ---- phase 2: appended copies and padding, (group, row) items over all threads ----
-    for (int it = threadIdx.x; it < NT * nr; it += nthr) {
-        const int gt = it % NT, r = it / NT;
-        const int g = NH + gt;
-        const uint8_t cf = tf[gt];
-        if (!cf) {
-            gather_group(g, r, r + 1, false);
-            continue;
-        }
-        uint8_t* o = out + (size_t)(r0 + r) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3));
-        if (cf == 2) {
-            // all 16 slots repeat one channel: replicate its value
-            const uint32_t q1 = (uint32_t)(qs[(size_t)r * KQ + ts[gt * 16]]);
-            if (BITS == 8) {
-                const uint32_t w = q1 * 0x01010101u;
-                *reinterpret_cast<v4u*>(o) = v4u{w, w, w, w};
-            } else {
-                const uint32_t w = (q1 & 0xfu) * 0x11111111u;
-                *reinterpret_cast<v2u*>(o) = v2u{w, w};
-            }
-            continue;
-        }
-        const v4u* tp = reinterpret_cast<const v4u*>(ts + gt * 16);
-        const v4u t0 = tp[0], t1 = tp[1];
-        const int8_t* ql = reinterpret_cast<const int8_t*>(qs) + (size_t)r * KQ;
-        int q[16];
+    // ---- phase 2: appended copies and padding, (group, row) items over all threads, two per thread
+    //      and pass with the LDS reads of both issued before either is packed ----
+    constexpr int U = 2;
+    const int items = NT * nr;
+    for (int it0 = threadIdx.x; it0 < items; it0 += nthr * U) {
+        int gt[U], rr[U];
+        bool ok[U];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const uint32_t word = (i < 8) ? t0[i >> 1] : t1[(i - 8) >> 1];
-            const uint32_t j = (i & 1) ? (word >> 16) : (word & 0xffffu);
-            q[i] = (j == 0xffffu) ? 0 : (int)ql[j];
+        for (int u = 0; u < U; ++u) {
+            const int it = it0 + u * nthr;
+            const bool valid = it < items;
+            gt[u] = valid ? it % NT : 0;
+            rr[u] = valid ? it / NT : 0;
+            const uint8_t cf = valid ? tf[gt[u]] : (uint8_t)1;
+            ok[u] = valid && cf != 0;
+            if (valid && cf == 0) gather_group(NH + gt[u], rr[u], rr[u] + 1, false);
         }
-        pack_store(q, o);
+        v4u t0[U], t1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const v4u* tp = reinterpret_cast<const v4u*>(ts + gt[u] * 16);
+            t0[u] = tp[0];
+            t1[u] = tp[1];
+        }
+        int q[U][16];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int8_t* ql = reinterpret_cast<const int8_t*>(qs) + (size_t)rr[u] * KQ;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t word = (i < 8) ? t0[u][i >> 1] : t1[u][(i - 8) >> 1];
+                const uint32_t j = (i & 1) ? (word >> 16) : (word & 0xffffu);
+                q[u][i] = (j == 0xffffu) ? 0 : (int)ql[j];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) {
+                const int g = NH + gt[u];
+                pack_store(q[u], out + (size_t)(r0 + rr[u]) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3)));
+            }
     }
 }
 
