@@ -569,3 +569,25 @@ def test_linear_replayed_from_a_graph(bits):
     Wq_ref, s_w_ref = O.flatten_weights(L.W, lay.src_host, bits)
     acc_ref, _, _ = O.linear(Xh, lay.src_host, lay.rep_host, Wq_ref, s_w_ref, bits, want_y=False)
     np.testing.assert_array_equal(Ye.cpu().numpy(), acc_ref)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_more_tiles_than_compute_units(bits):
+    """272 tiles of 256 x 256 with ragged edges: on a 256-CU device the large-problem kernel walks a
+    second round (prefetching across the tile boundary) and finishes with half-height tiles."""
+    rng = np.random.default_rng(900 + bits)
+    M, N, Kpad = 17 * 256 - 20, 16 * 256 - 7, 160 if bits == 8 else 320
+    Xq, Wq = _rand_q(rng, M, Kpad, bits), _rand_q(rng, N, Kpad, bits)
+    ref = O.gemm_i32(Xq, Wq)
+    assert np.array_equal(_gemm_acc(Xq, Wq, bits), ref)
+    # the 2-byte staged epilogue of the same walk
+    Xd = torch.from_numpy(Xq if bits == 8 else O.pack_i4(Xq)).to(DEV)
+    Wd = torch.from_numpy(Wq if bits == 8 else O.pack_i4(Wq)).to(DEV)
+    Npad = N + 7                                               # rows of Y on 16-byte boundaries
+    Y = torch.zeros((M, Npad), dtype=torch.bfloat16, device=DEV)
+    s_x, s_w = scalar(0.01), scalar(0.003)
+    (fq.fq_gemm_i8 if bits == 8 else fq.fq_gemm_i4)(Xd, Wd, s_x, s_w, Y[:, :N])
+    torch.cuda.synchronize()
+    y_ref = O.dequant(ref, np.float32(0.01), np.float32(0.003))
+    assert rel_err(bf16_to_f64(Y[:, :N]), y_ref).max() <= 2.0 ** -8
+    assert not Y[:, N:].any()
