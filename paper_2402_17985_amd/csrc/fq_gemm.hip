@@ -194,6 +194,9 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
     constexpr int ROWB = FN * 32 * 2;                      // bytes per staged row
     constexpr int UNITS = ROWB / 16;
     constexpr int SW = (UNITS >= 8 ? 8 : UNITS) - 1;
+    // the swizzle advances once per 256 bytes of staged rows, so that the 8-byte writes of 32 lanes (one
+    // row each) spread over all 16-byte units of the 64 banks
+    constexpr int SWS = (ROWB >= 256) ? 0 : (ROWB == 128 ? 1 : 2);
     constexpr int ROWS_PER_INSTR = 64 / UNITS;
     static_assert(sizeof(vec_t) == 8 && (CH * 32) % ROWS_PER_INSTR == 0 && FM % CH == 0, "staging layout");
     const int lane = threadIdx.x & 63;
@@ -215,13 +218,13 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = convert_out<MODE, YDT>(acc[i][j], 4 * g + e, scale, hb, b4[e]);
                     const int u = g + 4 * j;
-                    *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ (m & SW)) << 4) + 8 * fhalf) = v;
+                    *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ ((m >> SWS) & SW)) << 4) + 8 * fhalf) = v;
                 }
         }
 #pragma unroll
         for (int t = 0; t < CH * 32 / ROWS_PER_INSTR; ++t) {
             const int m = t * ROWS_PER_INSTR + mr;
-            const int u = us ^ (m & SW);
+            const int u = us ^ ((m >> SWS) & SW);
             const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
             // the output is written once and not read by this kernel: a streaming store of whole 128-byte
             // lines keeps it from displacing the operand panels in L2 (partial-line streaming stores, as
@@ -937,8 +940,9 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
         // narrow outputs (N <= 128, the P V product of attention) and small problems use the 128x128 tile
         // long phases (10) where the operand registers allow it: INT8 and bf16 would hold four unpacked
-        // k-slices per phase and spill, so they keep two k-slices per phase (7)
-        v = (big_tiles >= 192 && N > 128) ? (MODE == MODE_I4 ? 10 : 7) : 6;
+        // k-slices per phase and spill, so they keep two k-slices per phase (7), as do reductions of
+        // only a few k-stages (attention's Q K^T)
+        v = (big_tiles >= 192 && N > 128) ? ((MODE == MODE_I4 && rowbytes >= 512) ? 10 : 7) : 6;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
