@@ -631,12 +631,20 @@ void launch_colabsmax(const void* X, int M, int K, int ld, bool accumulate, uint
     constexpr int VEC = Elem<DT>::VEC;
     if (!accumulate) fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(cmax, K, 0u);
     const int bx = (K + 64 * VEC - 1) / (64 * VEC);
-    // a workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves); aim at
-    // about 1024 workgroups, at most 512 rows each (more, smaller workgroups measured slower)
-    long long rpb = ((long long)M * bx + 1023) / 1024;
+    // A workgroup takes a multiple of 64 rows (16 loads in flight for each of its 4 waves).  Measured:
+    // long strips (a few hundred workgroups in all, each wave streaming 100+ rows) beat many short ones,
+    // and the strip height must not be a power of two: with power-of-two row strides (K = 4096 bf16)
+    // workgroups that start a power-of-two number of rows apart hit the same memory channels
+    // (3.1 TB/s at 128 or 512 rows, 4.6 TB/s at 448).  So: an odd multiple of 64, 448..704 rows,
+    // fewer when the matrix is too small to give about 64 workgroups.
+    long long rpb = ((long long)M * bx + 399) / 400;
     rpb = (rpb + 63) / 64 * 64;
-    if (rpb < 128) rpb = 128;
-    if (rpb > 512) rpb = 512;
+    if (rpb < 448) rpb = 448;
+    if (rpb > 704) rpb = 704;
+    long long cap = ((long long)M * bx / 64 + 63) / 64 * 64;
+    if (cap < 64) cap = 64;
+    if (rpb > cap) rpb = cap;
+    if ((rpb / 64) % 2 == 0) rpb += 64;
     dim3 grid(bx, (unsigned)((M + rpb - 1) / rpb));
     colabsmax_kernel<DT><<<grid, 256, 0, stream>>>(X, M, K, ld, (int)rpb, cmax);
 }
