@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of the dominant kernel (INT4 GEMM, average of its two launches per step) for
 # the default workload and kernel choice, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
 # by a plain 1 GiB copy in the same runs: profiles/pmc_traffic_bench_cfg3_m8192.txt.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.26e8}
+MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.56e8}
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (INT4 is widened to int8 on chip: same ceiling)
 BF16_PEAK_TFLOPS = 2500.0
