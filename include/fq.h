@@ -211,7 +211,8 @@ int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx,
  * packed in HBM and LDS and are widened to int8 in registers (gfx950 has no 4-bit MFMA).
  * M, N >= 1 arbitrary; Kpad a multiple of 32 with Kpad * 128 * 128 < 2^31.
  * s_x, s_w  device scalars read by the kernel (no host synchronization).
- * Y         device, row stride ldy >= N elements.
+ * Y         device, row stride ldy >= N elements.  2-byte outputs leave fastest when Y is 128-byte aligned
+ *           and ldy is a multiple of 64 elements (whole cache lines per row segment).
  * ------------------------------------------------------------------------------------------- */
 int fq_gemm_i8(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad,
                const float* s_x, const float* s_w, void* Y, int y_dtype, int ldy, void* stream);

@@ -203,6 +203,7 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
     const int frow = lane & 31, fhalf = lane >> 5;
     uint8_t* Yb = static_cast<uint8_t*>(Y);
     const int mr = lane / UNITS, us = lane % UNITS;
+    const bool whole_lines = (ldy & 63) == 0 && (col0 & 63) == 0 && (reinterpret_cast<uintptr_t>(Y) & 127) == 0;
 #pragma unroll
     for (int c = 0; c < FM / CH; ++c) {
 #pragma unroll
@@ -221,15 +222,29 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
                     *reinterpret_cast<vec_t*>(stage + m * ROWB + ((u ^ ((m >> SWS) & SW)) << 4) + 8 * fhalf) = v;
                 }
         }
+        // The output is written once and not read by this kernel: a streaming store keeps it from
+        // displacing the operand panels in L2 -- but only when the 128-byte row segments are whole cache
+        // lines; partial-line streaming stores are several times slower than ordinary ones.  (Two loops
+        // kept apart: merged, they become one ordinary store.)
+        uint8_t* ybase = Yb + ((size_t)(row0 + c * CH * 32) * ldy + col0) * 2;
+        if (whole_lines) {
+            asm volatile("; streaming stores begin");    // the markers keep the two arms from being merged
 #pragma unroll
-        for (int t = 0; t < CH * 32 / ROWS_PER_INSTR; ++t) {
-            const int m = t * ROWS_PER_INSTR + mr;
-            const int u = us ^ ((m >> SWS) & SW);
-            const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
-            // the output is written once and not read by this kernel: a streaming store of whole 128-byte
-            // lines keeps it from displacing the operand panels in L2 (partial-line streaming stores, as
-            // the unstaged path would issue, are several times slower than ordinary ones)
-            __builtin_nontemporal_store(d, reinterpret_cast<v4i*>(Yb + ((size_t)(row0 + c * CH * 32 + m) * ldy + col0) * 2 + (u << 4)));
+            for (int t = 0; t < CH * 32 / ROWS_PER_INSTR; ++t) {
+                const int m = t * ROWS_PER_INSTR + mr;
+                const int u = us ^ ((m >> SWS) & SW);
+                const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
+                __builtin_nontemporal_store(d, reinterpret_cast<v4i*>(ybase + (size_t)m * ldy * 2 + (u << 4)));
+            }
+            asm volatile("; streaming stores end");
+        } else {
+#pragma unroll
+            for (int t = 0; t < CH * 32 / ROWS_PER_INSTR; ++t) {
+                const int m = t * ROWS_PER_INSTR + mr;
+                const int u = us ^ ((m >> SWS) & SW);
+                const v4i d = *reinterpret_cast<const v4i*>(stage + m * ROWB + (us << 4));
+                *reinterpret_cast<v4i*>(ybase + (size_t)m * ldy * 2 + (u << 4)) = d;
+            }
         }
     }
 }
