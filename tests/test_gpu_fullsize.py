@@ -2,7 +2,8 @@
 (FqLinear defaults: automatic kernel choice, 128/256-channel row alignment, dynamic scale).
 
 What is compared: the flatten map, the quantized activations and weights and the scales in full
-(bit-exact); the int32 accumulators on sampled rows the oracle recomputes one by one (bit-exact)
+(bit-exact); the int32 accumulators on about 256 sampled rows and 256 sampled columns that the oracle
+recomputes (bit-exact)
 plus an exact int64 Freivalds identity over the whole matrix (acc r == Xq (Wq^T r) for a random
 vector r: any wrong accumulator changes the left side unless its r entry is 0, probability 2^-20
 per vector); the bf16 outputs on the sampled rows (relative 2^-8, see test_gpu_parity)."""
@@ -18,7 +19,7 @@ from tests.gpu_util import DEV, bf16_to_f64, rel_err, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _check_layer(cfg_name, idx, n_sample_rows=40, freivalds=2):
+def _check_layer(cfg_name, idx, n_sample_rows=256, n_sample_cols=256, freivalds=2):
     cfg = WL.CONFIGS[cfg_name]
     print(f"[fullsize] generating {cfg_name} layer {idx}", flush=True)
     L = WL.make_layer(cfg, idx)
@@ -52,6 +53,9 @@ def _check_layer(cfg_name, idx, n_sample_rows=40, freivalds=2):
     acc_o = O.gemm_i32(Xq_o[rows], Wq_o)
     assert np.array_equal(acc_g[rows], acc_o)
     print(f"[fullsize]   {len(rows)} sampled accumulator rows equal the oracle's", flush=True)
+    cols_s = np.unique(np.concatenate([[0, sp.N - 1], rng.integers(0, sp.N, n_sample_cols)]))
+    assert np.array_equal(acc_g[:, cols_s], O.gemm_i32(Xq_o, Wq_o[cols_s]))
+    print(f"[fullsize]   {len(cols_s)} sampled accumulator columns equal the oracle's", flush=True)
     # --- every accumulator at once: exact Freivalds identity in int64 ---
     for rep_i in range(freivalds):
         r = rng.integers(0, 1 << 20, sp.N).astype(np.int64)
@@ -89,17 +93,17 @@ def test_benchmark_layers_full_size(cfg, idx):
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_cfg4_opt13b_layers_full_size(idx):
     """OPT-13B-style layer, M = 8192: QKV and out projections INT8, FC1 / FC2 INT4."""
-    _check_layer("cfg4", idx, n_sample_rows=24, freivalds=1)
+    _check_layer("cfg4", idx, freivalds=1)
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_cfg5_llama65b_layers_full_size(idx):
     """LLaMA-65B-scale layer, M = 16384: attention projections INT8, FFN INT4."""
-    _check_layer("cfg5", idx, n_sample_rows=16, freivalds=1)
+    _check_layer("cfg5", idx, freivalds=1)
 
 
 @pytest.mark.parametrize("idx", [0, 1])
 def test_paper_table5_shape_full_size(idx):
     """The shape of the paper's operator measurement (Table 5): 8 x 2048 tokens, 4096 -> 4096, about 1024
     expanded channels; INT8 and INT4."""
-    _check_layer("cfgP", idx, n_sample_rows=24, freivalds=1)
+    _check_layer("cfgP", idx, freivalds=1)
