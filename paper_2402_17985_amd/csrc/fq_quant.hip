@@ -4,19 +4,20 @@
 // channel holds x/n), Eq. 4 (weight channel repeated), Sec. 2.1 Eq. 1 (per-tensor scale
 // s = max|.| / qmax, round, here round-half-even, then clamp).
 //
-// Three kernels, all bandwidth bound:
-//   colabsmax      per input channel max|x| over the rows (64-wide wave reads 1 KiB of a row per
-//                  instruction; per-thread running max; one atomic max per column per block;
-//                  the max of non-negative floats is taken on their bit patterns, so the result
-//                  does not depend on the order of the updates)
-//   scale          per-tensor absmax a' by wavefront reductions, the scale s, and the per-slot
-//                  multiplier m_p = fl32(qmax / (n_p * a')) (float64 quotient)
-//   flatten_quant  each thread owns 16 consecutive flattened slots for a strip of rows: the map
-//                  and multipliers are read once into registers, then per row 16 values are
-//                  read (one contiguous 32/64-byte vector read when the slots are an identity
-//                  run, else a gather that hits the cache lines the neighbours just read),
-//                  multiplied, rounded, clamped, packed and stored as one 16-byte (INT8) or
-//                  8-byte (INT4) write.
+// The kernels, all bandwidth or latency bound:
+//   colabsmax           per input channel max|x| over the rows (64-wide wave reads 1 KiB of a row per
+//                       instruction; per-thread running max; one atomic max per column per block;
+//                       the max of non-negative floats is taken on their bit patterns, so the
+//                       result does not depend on the order of the updates)
+//   scale               per-tensor absmax a' by wavefront reductions, the scale s, the per-slot
+//                       multiplier m_p = fl32(qmax / (n_p * a')) (float64 quotient), and two flags
+//                       per group of 16 slots that tell the quantizer which path a group may take
+//   flatten_quant_rows  the quantizer of the equal split: a workgroup owns a strip of rows, reads the
+//                       head of the map with vector loads, keeps the quantized bytes in LDS and lets
+//                       the appended copies take their values from there
+//   flatten_quant       the general form (one thread per 16 slots and strip of rows, every slot
+//                       gathered from global memory): the peel split of Eq. 3 as printed, and layers
+//                       too wide for the row-strip kernel's LDS budget
 #include "fq_internal.h"
 
 namespace fq {
