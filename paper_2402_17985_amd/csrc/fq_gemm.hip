@@ -22,13 +22,18 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on
 // a contiguous band of tiles, walked in groups of GROUP_M tile-rows for L2 reuse.
 //
-// Two pipelines:
+// Two kernels:
 //   gemm_dma_kernel   global -> LDS directly (global_load_lds_dwordx4: a wave fills one contiguous
 //                     1 KiB block of the stage per instruction, each lane fetching the global chunk
 //                     that belongs at its LDS position), stage t+1 in flight while stage t is
-//                     multiplied; MFMA operands double-buffered in registers so that the LDS reads
-//                     of k-slice s+1 are issued before the MFMAs of k-slice s.  Large problems.
-//   gemm_reg_kernel   global -> registers -> LDS, smaller tiles.  Small problems.
+//                     multiplied.  Three schedules of the multiply (template parameter PIPE): the
+//                     ping-pong of two wave groups (large problems), and two schedules that interleave
+//                     the LDS reads of k-slice s+1 with the MFMAs of k-slice s in every wave.  With
+//                     the ping-pong schedule one workgroup per CU walks its tiles and fetches the next
+//                     tile's first stage while it stores the current one.  Batched products put the
+//                     batch index in the grid's y dimension.
+//   gemm_reg_kernel   global -> registers -> LDS, 128x128 tile; a selectable variant.
+// This file is compiled once per operand mode (see the end of the file).
 #include <type_traits>
 
 #include "fq_internal.h"
