@@ -145,6 +145,7 @@ def main():
     # ---------------- per-kernel breakdown (HIP events, same process) ----------------
     rows = []
     t_bf16_total = 0.0
+    t_vendor_total = 0.0
     dom = dict(flops=0.0, ms=0.0, launches=0)       # the dominant kernel: INT4 GEMM (else INT8)
     dom_bits = 4 if any(d["spec"].bits == 4 for d in layers) else 8
     fqa = dict(bytes=0.0, ms=0.0)
@@ -165,6 +166,10 @@ def main():
         t_lin = event_time_ms(torch, f_lin, args.steps)
         t_bf = event_time_ms(torch, f_bf, args.steps)
         t_bf16_total += t_bf
+        # reference only: the vendor library's bf16 GEMM (through torch.matmul) on the same operands
+        f_vendor = lambda: torch.matmul(d["Xb"], d["Wb"].t(), out=d["Ybf"])
+        t_vendor = event_time_ms(torch, f_vendor, args.steps)
+        t_vendor_total += t_vendor
         flops = 2.0 * sp.M * Kpad * sp.N
         # algorithmic HBM bytes of flatten-quantize: X read once (static) or twice (dynamic), Xq written
         act_bytes = sp.M * sp.K * d["X"].element_size() * (1 if args.static else 2) + sp.M * cols
@@ -176,7 +181,7 @@ def main():
         fqa["ms"] += t_act
         row = dict(layer=d["name"], bits=sp.bits, M=sp.M, K=sp.K, N=sp.N, Kpad=Kpad,
                    ms_flatten_quant=round(t_act, 4), ms_gemm=round(t_gemm, 4), ms_linear=round(t_lin, 4),
-                   ms_gemm_bf16=round(t_bf, 4),
+                   ms_gemm_bf16=round(t_bf, 4), ms_vendor_bf16=round(t_vendor, 4),
                    gemm_tops=round(flops / t_gemm / 1e9, 1),
                    gemm_pct_int8_peak=round(100 * flops / t_gemm / 1e9 / INT8_PEAK_TOPS, 2),
                    bf16_tflops=round(2.0 * sp.M * sp.K * sp.N / t_bf / 1e9, 1),
@@ -301,6 +306,8 @@ def main():
         "effective_tops": round(ops_eff / (t_step_ms * 1e-3) / 1e12, 2),
         "speedup_vs_bf16": round(t_bf16_total / t_step_ms, 3),
         "ms_bf16_gemm_same_shapes": round(t_bf16_total, 4),
+        "speedup_vs_vendor_bf16": round(t_vendor_total / t_step_ms, 3),
+        "ms_vendor_bf16_gemm_same_shapes": round(t_vendor_total, 4),
         "roofline": roofline,
         "flatten_quant_roofline": flatten_roofline,
         "cpu_baseline": cpu,
