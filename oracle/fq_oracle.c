@@ -669,3 +669,59 @@ void fqo_dequant_bias(const int32_t *acc, int rows, int N, float s_x, float s_w,
         for (int n = 0; n < N; ++n)
             y_out[(size_t)i * N + n] = (double)acc[(size_t)i * N + n] * (double)s_x * (double)s_w + (double)bias[n];
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Second storage format of the 4-bit quantized tensors: each value q in [-8, 7] is stored as the
+ * 6-bit floating-point code E3M2 (1 sign, 3 exponent bits with bias 3, 2 mantissa bits; value
+ * (-1)^s * 2^(e-3) * (1 + m/4) for e >= 1, (-1)^s * 2^-2 * (m/4) for e = 0; no infinities or NaNs)
+ * that represents the integer q exactly, 6 bits per slot, packed as a little-endian bit stream
+ * along the flattened-channel axis (slot p occupies bits [6p, 6p+6) of its row; 16 slots = 12
+ * bytes).  The paper leaves the storage of its 4-bit operands to its GEMM library; this format is
+ * what the 6-bit matrix instructions of the target consume.  Kpad must be a multiple of 16.
+ * ---------------------------------------------------------------------------------------- */
+static int e3m2_code(int q)
+{
+    /* |q| = 0..8 as 2^(e-3) * (1 + m/4): 1 = 2^0, 2, 3 = 2 * 1.5, 4, 5 = 4 * 1.25, 6, 7, 8 = 2^3 */
+    int a = q < 0 ? -q : q, e = 0, m = 0;
+    if (a >= 1) {
+        e = 3;
+        while ((2 << (e - 3)) <= a) ++e;             /* 2^(e-3) <= a < 2^(e-2) */
+        m = (4 * a) / (1 << (e - 3)) - 4;            /* a = 2^(e-3) * (1 + m/4), exact for a <= 8 */
+    }
+    return ((q < 0) ? 0x20 : 0) | (e << 2) | m;
+}
+
+int fqo_pack_e3m2(const int8_t *q, long long rows, int Kpad, uint8_t *out /* rows x Kpad*3/4 */)
+{
+    if (!q || !out || rows <= 0 || Kpad <= 0 || Kpad % 16) return FQO_ERR_ARG;
+    long long rb = (long long)Kpad * 3 / 4;
+    memset(out, 0, (size_t)(rows * rb));
+    for (long long r = 0; r < rows; ++r)
+        for (int p = 0; p < Kpad; ++p) {
+            int v = q[r * Kpad + p];
+            if (v < -8 || v > 8) return FQO_ERR_ARG;
+            int c = e3m2_code(v);
+            long long bit = 6LL * p;
+            for (int b = 0; b < 6; ++b)
+                if ((c >> b) & 1) out[r * rb + (bit + b) / 8] |= (uint8_t)(1u << ((bit + b) % 8));
+        }
+    return FQO_OK;
+}
+
+/* Decodes by the format's definition (not by inverting the table above). */
+int fqo_unpack_e3m2(const uint8_t *packed, long long rows, int Kpad, double *out /* rows x Kpad */)
+{
+    if (!packed || !out || rows <= 0 || Kpad <= 0 || Kpad % 16) return FQO_ERR_ARG;
+    long long rb = (long long)Kpad * 3 / 4;
+    for (long long r = 0; r < rows; ++r)
+        for (int p = 0; p < Kpad; ++p) {
+            int c = 0;
+            long long bit = 6LL * p;
+            for (int b = 0; b < 6; ++b)
+                if ((packed[r * rb + (bit + b) / 8] >> ((bit + b) % 8)) & 1) c |= 1 << b;
+            int sgn = c >> 5, e = (c >> 2) & 7, m = c & 3;
+            double v = (e == 0) ? 0.25 * (m / 4.0) : ldexp(1.0 + m / 4.0, e - 3);
+            out[r * Kpad + p] = sgn ? -v : v;
+        }
+    return FQO_OK;
+}

@@ -340,3 +340,24 @@ def dequant_bias(acc, s_x, s_w, bias):
     lib().fqo_dequant_bias(_p(acc, ctypes.c_int32), rows, N, ctypes.c_float(s_x), ctypes.c_float(s_w),
                            _p(bias, ctypes.c_float), _p(out, ctypes.c_double))
     return out
+
+
+def pack_e3m2(q):
+    """4-bit values as packed 6-bit E3M2 codes: int8 [rows, Kpad] -> uint8 [rows, Kpad * 3 / 4]."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    rows, Kpad = q.shape
+    out = np.empty((rows, Kpad * 3 // 4), dtype=np.uint8)
+    rc = lib().fqo_pack_e3m2(_p(q, ctypes.c_int8), ctypes.c_longlong(rows), Kpad, _p(out, ctypes.c_uint8))
+    _check(rc, "fqo_pack_e3m2")
+    return out
+
+
+def unpack_e3m2(packed):
+    """Decodes packed E3M2 codes by the format's definition: uint8 [rows, Kpad*3/4] -> float64 [rows, Kpad]."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    rows, rb = packed.shape
+    Kpad = rb * 4 // 3
+    out = np.empty((rows, Kpad), dtype=np.float64)
+    rc = lib().fqo_unpack_e3m2(_p(packed, ctypes.c_uint8), ctypes.c_longlong(rows), Kpad, _p(out, ctypes.c_double))
+    _check(rc, "fqo_unpack_e3m2")
+    return out

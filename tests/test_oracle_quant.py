@@ -173,3 +173,27 @@ def test_weights_quantize_then_repeat():
     assert s_w4 == np.float32(1.0 / 7.0)
     Wz, s_z = O.flatten_weights(np.zeros((2, 3), np.float32), src, 8)
     assert (Wz == 0).all() and s_z == np.float32(1.0)
+
+
+def test_e3m2_storage_hand_codes_and_round_trip():
+    """The 6-bit E3M2 storage of 4-bit values.  Hand codes from the format (sign | exponent, bias 3 |
+    two mantissa bits): 1 = 2^0 -> e=3 m=0 -> 0b001100; 3 = 2 * 1.5 -> e=4 m=2 -> 0b010010;
+    5 = 4 * 1.25 -> 0b010101; 7 = 4 * 1.75 -> 0b010111; -8 = -(2^3) -> 0b111000; 0 -> 0.
+    Bit stream, little endian: slots (1, 3, 5, 7) -> 0x0C | 0x12 << 6 | 0x15 << 12 | 0x17 << 18."""
+    q = np.zeros((1, 16), dtype=np.int8)
+    q[0, :6] = [1, 3, 5, 7, -8, -1]
+    got = O.pack_e3m2(q)
+    word = 0x0C | (0x12 << 6) | (0x15 << 12) | (0x17 << 18) | (0x38 << 24) | (0x2C << 30)
+    want = np.frombuffer(int(word).to_bytes(12, "little"), dtype=np.uint8)
+    assert got.shape == (1, 12) and got[0].tolist() == want.tolist()
+    # every representable value decodes, by the format's definition, to itself
+    allq = np.tile(np.arange(-8, 8, dtype=np.int8), (3, 2))              # [3, 32]
+    dec = O.unpack_e3m2(O.pack_e3m2(allq))
+    np.testing.assert_array_equal(dec, allq.astype(np.float64))
+    # slots are independent 6-bit fields: changing one slot changes only its bits
+    a, b = allq.copy(), allq.copy()
+    b[1, 5] = 7 if a[1, 5] != 7 else 6
+    diff = np.flatnonzero(O.pack_e3m2(a)[1] != O.pack_e3m2(b)[1])
+    assert set(diff.tolist()) <= {3, 4}                                  # bits 30..35 live in bytes 3 and 4
+    with pytest.raises(O.OracleError):
+        O.pack_e3m2(np.full((1, 16), 9, dtype=np.int8))
