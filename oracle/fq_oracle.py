@@ -352,6 +352,28 @@ def pack_e3m2(q):
     return out
 
 
+def pack_e3m2_blocked(q):
+    """The same codes in the layout of the 6-bit GEMM: int8 [rows, Kpad] (Kpad a multiple of 128) -> uint8
+    [Kpad / 128, rows, 96].  Block t holds 96 bytes for every row: two 48-byte groups (codes 128 t + 64 s ..
+    + 63, s = 0, 1).  The 24-byte stream of each 32-code unit a of a group is split into its first 16 bytes
+    X_a and last 8 bytes Y_a, and the group is stored X_a Y_a Y_b X_b with (a, b) = (0, 1) in rows whose
+    index has bit 4 clear and (1, 0) in rows with bit 4 set."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    rows, Kpad = q.shape
+    if Kpad % 128:
+        raise ValueError("Kpad must be a multiple of 128")
+    nb = Kpad // 128
+    stream = pack_e3m2(q).reshape(rows, nb, 2, 2, 24)        # [row, block, group, unit, stream byte]
+    out = np.empty((nb, rows, 96), dtype=np.uint8)
+    for r in range(rows):
+        a, b = (0, 1) if (r & 16) == 0 else (1, 0)
+        for t in range(nb):
+            for s in range(2):
+                ua, ub = stream[r, t, s, a], stream[r, t, s, b]
+                out[t, r, 48 * s:48 * s + 48] = np.concatenate([ua[:16], ua[16:], ub[16:], ub[:16]])
+    return out
+
+
 def unpack_e3m2(packed):
     """Decodes packed E3M2 codes by the format's definition: uint8 [rows, Kpad*3/4] -> float64 [rows, Kpad]."""
     packed = np.ascontiguousarray(packed, dtype=np.uint8)

@@ -197,3 +197,38 @@ def test_e3m2_storage_hand_codes_and_round_trip():
     assert set(diff.tolist()) <= {3, 4}                                  # bits 30..35 live in bytes 3 and 4
     with pytest.raises(O.OracleError):
         O.pack_e3m2(np.full((1, 16), 9, dtype=np.int8))
+
+
+def test_e3m2_blocked_layout_hand_addresses():
+    """The blocked E3M2 layout: the 96 bytes of (block t, row r) sit at (t * rows + r) * 96; a 48-byte group
+    is X_a Y_a Y_b X_b (X: stream bytes 0..15 of a 32-code unit, Y: bytes 16..23), units in order (0, 1) for
+    rows with bit 4 clear, (1, 0) for rows with bit 4 set.  Hand case, 18 rows x 256 slots, zero except:
+    q[1, 0] = 1 (code 0x0C; block 0, group 0, unit 0, stream byte 0 -> X_0 at +0)       -> byte 1*96 = 96;
+    q[2, 128] = -8 (code 0x38; block 1, group 0, unit 0, stream byte 0)                  -> byte (18+2)*96 = 1920;
+    q[0, 255] = 3 (code 0x12; block 1, group 1, unit 1, code 31 = stream bits 186..191 = byte 23 = Y_1[7],
+                   Y_1 at +24)                                       -> byte 18*96 + 48 + 31 = 1807, value 0x12 << 2;
+    q[17, 0] = 1 (row bit 4 set: unit 0 is stored second, X_0 at +32)                    -> byte 17*96 + 32 = 1664;
+    q[16, 32] = 1 (unit 1, stored first in this row, X_1 at +0)                          -> byte 16*96 = 1536;
+    q[16, 31] = 5 (code 0x15; unit 0, code 31 -> Y_0[7], Y_0 at +24 in this row)         -> byte 1536 + 31 = 1567."""
+    q = np.zeros((18, 256), dtype=np.int8)
+    q[1, 0], q[2, 128], q[0, 255], q[17, 0], q[16, 32], q[16, 31] = 1, -8, 3, 1, 1, 5
+    blk = O.pack_e3m2_blocked(q)
+    assert blk.shape == (2, 18, 96)
+    want = np.zeros(2 * 18 * 96, dtype=np.uint8)
+    want[96], want[1920], want[1807], want[1664], want[1536], want[1567] = 0x0C, 0x38, 0x12 << 2, 0x0C, 0x0C, 0x15 << 2
+    assert np.flatnonzero(blk.reshape(-1)).tolist() == np.flatnonzero(want).tolist()
+    assert blk.reshape(-1).tolist() == want.tolist()
+    # a permutation of the plain stream's bytes, the same for all rows of equal bit 4 and for all blocks
+    rng = np.random.default_rng(5)
+    q = rng.integers(-8, 8, (40, 640), dtype=np.int8)
+    blk, stream = O.pack_e3m2_blocked(q), O.pack_e3m2(q)
+    fwd = list(range(0, 24)) + list(range(40, 48)) + list(range(24, 40))       # X0 Y0 Y1 X1
+    rev = list(range(24, 48)) + list(range(16, 24)) + list(range(0, 16))       # X1 Y1 Y0 X0
+    for t in range(5):
+        for r in range(40):
+            piece = stream[r, 96 * t:96 * t + 96]
+            perm = fwd if (r & 16) == 0 else rev
+            want_piece = np.concatenate([piece[:48][perm], piece[48:][perm]])
+            assert blk[t, r].tolist() == want_piece.tolist()
+    with pytest.raises(ValueError):
+        O.pack_e3m2_blocked(np.zeros((2, 192), dtype=np.int8))
