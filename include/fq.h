@@ -233,6 +233,40 @@ int fq_gemm_i4_bias(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad
                     void* Y, int y_dtype, int ldy, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * fq_gemm_i4_e3m2 — the 4-bit layer's integer GEMM on operands stored as 6-bit codes.
+ * Sec. 5.1 (4-bit GEMM of the quantized linear layer), Eq. 1 with k = 4.  What is computed is exactly
+ * fq_gemm_i4_bias: the quantized values are the same integers in [-8, 7].  Only their storage differs,
+ * which lets the product run on gfx950's 6-bit matrix pipe at twice the INT8 rate (there is no 4-bit
+ * integer MFMA; the nibble path widens to int8):
+ *
+ *   storage  the value q of slot p is held as the 6-bit E3M2 floating-point code of the integer q
+ *            (sign, 3 exponent bits with bias 3, 2 mantissa bits; every integer in [-8, 8] is exactly
+ *            representable: 0 -> 0, |q| -> exponent floor(log2|q|) + 3, top two fraction bits of |q|).
+ *            Layout: blocked along the flattened-channel axis.  Block t holds, for row 0, 1, ... in turn,
+ *            96 bytes with that row's codes p = 128 t .. 128 t + 127; byte address of a row's piece:
+ *            (t * rows + row) * 96; total size rows * 3 Kpad / 4 bytes.  The piece is two 48-byte groups of
+ *            64 codes, each group two units of 32 codes.  A unit's codes form a little-endian bit stream of
+ *            24 bytes (code u of the unit in bits 6u .. 6u+5; bit b is bit b%8 of byte b/8), split into
+ *            its first 16 bytes X and last 8 bytes Y.  A group is stored X_a Y_a Y_b X_b, with (a, b) =
+ *            (0, 1) in rows whose index has bit 4 clear and (1, 0) in rows with bit 4 set.
+ *            (Why: a k-stage of a GEMM tile is one contiguous run of whole cache lines, every lane of the
+ *            matrix instruction finds its 24 bytes as one aligned 16-byte and one aligned 8-byte piece,
+ *            and the LDS reads of 32 consecutive rows are free of bank conflicts.)
+ *   product  every product of two codes is an integer of magnitude <= 64 and the fp32 accumulator of
+ *            the MFMA is exact below 2^24 > 64 Kpad, so acc[i,n] equals the int32 accumulator of
+ *            fq_gemm_i4 bit for bit; the epilogue (scales, bias, rounding, FQ_I32 output) is the same.
+ *
+ * Produced by fq_flatten_weights / fq_flatten_quant_act / fq_flatten_weights_split / fq_linear[_bias]
+ * when called with bits = FQ_BITS_I4_E3M2 (the 4-bit quantizer of Eq. 1, E3M2 storage; Wq then has to be
+ * in this storage too).  Kpad must be a multiple of 128 (whole blocks; a plan made with align = 128).
+ * The peel split has no E3M2 form (FQ_ERR_DTYPE).  bias may be NULL.
+ * ------------------------------------------------------------------------------------------- */
+#define FQ_BITS_I4_E3M2 6
+int fq_gemm_i4_e3m2(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad,
+                    const float* s_x, const float* s_w, const float* bias,
+                    void* Y, int y_dtype, int ldy, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * fq_bmm_i8 / fq_bmm_i4 — the batched form of the integer GEMM (Sec. 5.1: the quantized BMM function
  * that stands beside the quantized linear layer, for attention's two products).  The paper gives
  * no detail beyond INT8 / INT4 operands; the reading taken: per-tensor scales over the whole batched
@@ -294,6 +328,9 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)
  *   3: as 0 with 64-byte k-stages        4: as 0 with 4 waves (128x128 per wave)
  *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies
+ * fq_gemm_i4_e3m2 has two kernels of its own, both with 256x256 tiles: variant 0 = 8 waves in the ping-pong
+ * schedule (wave tile 128x64); any other value = 4 waves with 128x128 wave tiles, LDS reads interleaved
+ * between the MFMAs (the default).
  * Every variant computes the same values.  Returns FQ_ERR_RANGE for an unknown variant.
  * ------------------------------------------------------------------------------------------- */
 int fq_gemm_select(int variant);

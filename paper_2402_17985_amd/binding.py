@@ -24,7 +24,8 @@ SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
            "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
            "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel",
-           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias"]
+           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_gemm_i4_e3m2"]
+FQ_BITS_I4_E3M2 = 6   # the 4-bit quantizer with its values stored as 6-bit E3M2 codes
 
 
 class FqError(RuntimeError):
@@ -72,7 +73,7 @@ def lib() -> ctypes.CDLL:
     for f in (L.fq_bmm_i8, L.fq_bmm_i4):
         f.argtypes = [vp, vp, c_int, c_int, c_int, c_int, ctypes.c_longlong, ctypes.c_longlong, vp, vp, vp, c_int,
                       c_int, ctypes.c_longlong, vp]
-    for f in (L.fq_gemm_i8_bias, L.fq_gemm_i4_bias):
+    for f in (L.fq_gemm_i8_bias, L.fq_gemm_i4_bias, L.fq_gemm_i4_e3m2):
         f.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, c_int, c_int, vp]
     L.fq_linear_bias.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, vp, c_int, c_int, vp, vp,
                                  c_int, c_int, vp, c_size_t, vp]
@@ -274,12 +275,22 @@ def fq_gemm_i4_bias(Xq, Wq, s_x, s_w, bias, Y, stream=None) -> None:
     _gemm_bias(lib().fq_gemm_i4_bias, Xq, Wq, M, Wq.shape[0], 2 * half, s_x, s_w, bias, Y, stream)
 
 
+def fq_gemm_i4_e3m2(Xq, Wq, s_x, s_w, bias, Y, stream=None) -> None:
+    """Xq uint8 [Kpad / 128, M, 96], Wq uint8 [Kpad / 128, N, 96] (k-blocked 6-bit E3M2 codes of 4-bit values)
+    -> Y [M, N]."""
+    if Xq.dim() != 3 or Wq.dim() != 3 or Xq.shape[2] != 96 or Wq.shape[2] != 96 or Xq.shape[0] != Wq.shape[0]:
+        raise ValueError("E3M2 operands are [Kpad / 128, rows, 96] byte arrays")
+    if not (Xq.is_contiguous() and Wq.is_contiguous()):
+        raise ValueError("E3M2 operands must be contiguous")
+    _gemm_bias(lib().fq_gemm_i4_e3m2, Xq, Wq, Xq.shape[1], Wq.shape[1], 128 * Xq.shape[0], s_x, s_w, bias, Y, stream)
+
+
 def fq_linear_bias(X, src_idx, rep, Wq, s_w, bias, bits: int, Y, workspace, absmax_in=None, stream=None) -> None:
     _dev2d(X, "X")
     _dev2d(Y, "Y")
     M, K = X.shape
     Kpad = src_idx.numel()
-    N = Wq.shape[0]
+    N = Wq.shape[1] if Wq.dim() == 3 else Wq.shape[0]      # E3M2 weights are [Kpad / 128, N, 96]
     if bias is not None and (bias.numel() != N or _dtype_code(bias) != FQ_F32 or not bias.is_contiguous()):
         raise ValueError("bias must be a contiguous fp32 tensor of N elements")
     _check(lib().fq_linear_bias(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(), rep.data_ptr(),
@@ -324,7 +335,7 @@ def fq_linear(X, src_idx, rep, Wq, s_w, bits: int, Y, workspace, absmax_in=None,
     _dev2d(Y, "Y")
     M, K = X.shape
     Kpad = src_idx.numel()
-    N = Wq.shape[0]
+    N = Wq.shape[1] if Wq.dim() == 3 else Wq.shape[0]      # E3M2 weights are [Kpad / 128, N, 96]
     _check(lib().fq_linear(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(), rep.data_ptr(), Kpad,
                            Wq.data_ptr(), s_w.data_ptr(), N, bits, _ptr(absmax_in), Y.data_ptr(), _dtype_code(Y),
                            Y.stride(0), workspace.data_ptr(), workspace.numel() * workspace.element_size(),

@@ -11,6 +11,7 @@ OUT = os.path.join(HERE, "libfq.so")
 SOURCES = [("fq_gemm.hip", ["-DFQ_GEMM_MODE=1"], "fq_gemm_i4.o"),
            ("fq_gemm.hip", ["-DFQ_GEMM_MODE=0"], "fq_gemm_i8.o"),
            ("fq_gemm.hip", ["-DFQ_GEMM_MODE=2"], "fq_gemm_bf16.o"),
+           ("fq_gemm.hip", ["-DFQ_GEMM_MODE=3"], "fq_gemm_f6.o"),
            ("fq_api.hip", [], "fq_api.o"), ("fq_quant.hip", [], "fq_quant.o"),
            ("fq_gemm_select.hip", [], "fq_gemm_select.o")]
 # -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions

@@ -40,11 +40,20 @@ int check_matrix(const char* what, const void* p, int dtype, int rows, int K, in
     return FQ_OK;
 }
 
+// bytes of one row of a quantized array: a byte, a nibble or a 6-bit code per slot
+size_t quantized_row_bytes(int Kpad, int bits)
+{
+    return bits == 8 ? (size_t)Kpad : (bits == 4 ? (size_t)Kpad / 2 : (size_t)Kpad / 4 * 3);
+}
+
 int check_map(const int32_t* src_idx, int Kpad, int bits)
 {
     if (!src_idx) return fail(FQ_ERR_NULL, "src_idx is NULL");
-    if (bits != 8 && bits != 4) return fail(FQ_ERR_DTYPE, "bits = %d, must be 8 or 4", bits);
+    if (bits != 8 && bits != 4 && bits != FQ_BITS_I4_E3M2)
+        return fail(FQ_ERR_DTYPE, "bits = %d, must be 8, 4 or %d (4-bit values in E3M2 storage)", bits, FQ_BITS_I4_E3M2);
     if (Kpad <= 0 || Kpad % 32 != 0) return fail(FQ_ERR_SHAPE, "Kpad = %d must be a positive multiple of 32", Kpad);
+    if (bits == FQ_BITS_I4_E3M2 && Kpad % 128 != 0)
+        return fail(FQ_ERR_SHAPE, "Kpad = %d must be a multiple of 128 for E3M2 storage", Kpad);
     if (Kpad >= 131072) return fail(FQ_ERR_RANGE, "Kpad = %d: int32 accumulators could overflow (needs Kpad < 131072)", Kpad);
     if (!aligned16(src_idx)) return fail(FQ_ERR_ALIGN, "src_idx is not 16-byte aligned");
     return FQ_OK;
@@ -247,8 +256,8 @@ size_t fq_weights_workspace_bytes(int K, int Kpad) { return fq_act_workspace_byt
 
 size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits)
 {
-    if (M <= 0 || K <= 0 || Kpad <= 0 || (bits != 8 && bits != 4)) return 0;
-    const size_t xq = round_up((size_t)M * (bits == 8 ? (size_t)Kpad : (size_t)Kpad / 2), 256);
+    if (M <= 0 || K <= 0 || Kpad <= 0 || (bits != 8 && bits != 4 && bits != FQ_BITS_I4_E3M2)) return 0;
+    const size_t xq = round_up((size_t)M * quantized_row_bytes(Kpad, bits), 256);
     return xq + fq_act_workspace_bytes(K, Kpad);
 }
 
@@ -352,6 +361,16 @@ int fq_gemm_i4(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, con
     return gemm_common(Xq, Wq, M, N, Kpad, 4, s_x, s_w, nullptr, Y, y_dtype, ldy, stream);
 }
 
+int fq_gemm_i4_e3m2(const uint8_t* Xq, const uint8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+                    const float* bias, void* Y, int y_dtype, int ldy, void* stream)
+{
+    if (Kpad > 0 && Kpad % 128 != 0) {
+        clear_error();
+        return fail(FQ_ERR_SHAPE, "Kpad = %d must be a multiple of 128 for E3M2 storage", Kpad);
+    }
+    return gemm_common(Xq, Wq, M, N, Kpad, FQ_BITS_I4_E3M2, s_x, s_w, bias, Y, y_dtype, ldy, stream);
+}
+
 int fq_gemm_i8_bias(const int8_t* Xq, const int8_t* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
                     const float* bias, void* Y, int y_dtype, int ldy, void* stream)
 {
@@ -372,7 +391,7 @@ int bmm_common(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad
     clear_error();
     if (int rc = check_gemm(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy)) return rc;
     if (batch < 1 || batch > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", batch);
-    const long long rowbytes = bits == 8 ? Kpad : Kpad / 2;
+    const long long rowbytes = (long long)quantized_row_bytes(Kpad, bits);
     if (stride_a < (long long)M * rowbytes || stride_b < (long long)N * rowbytes)
         return fail(FQ_ERR_SHAPE, "operand batch stride smaller than one matrix (%lld, %lld bytes)", stride_a, stride_b);
     if (stride_a % 16 != 0 || stride_b % 16 != 0)
@@ -421,7 +440,7 @@ int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx, const int3
         return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
                     fq_linear_workspace_bytes(M, K, Kpad, bits));
     uint8_t* base = static_cast<uint8_t*>(workspace);
-    const size_t xq_bytes = round_up((size_t)M * (bits == 8 ? (size_t)Kpad : (size_t)Kpad / 2), 256);
+    const size_t xq_bytes = round_up((size_t)M * quantized_row_bytes(Kpad, bits), 256);
     void* Xq = base;
     ActWorkspace ws = carve_act_workspace(base + xq_bytes, K, Kpad);
     float* s_x = ws.scalars + 1;

@@ -46,8 +46,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 
-enum { MODE_I8 = 0, MODE_I4 = 1, MODE_BF16 = 2 };
+enum { MODE_I8 = 0, MODE_I4 = 1, MODE_BF16 = 2, MODE_F6 = 3 };   // F6: 4-bit values stored as 6-bit E3M2 codes
 
 #define FQ_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define FQ_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -77,6 +79,7 @@ __device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
 
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
+template <> struct Acc<MODE_F6> { typedef v16f type; };      // exact integers below 2^24 held in fp32
 
 __device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n);
 
@@ -762,6 +765,350 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
 }
 
 // =============================================================================================
+// gemm_f6_kernel: 4-bit operands stored as 6-bit E3M2 codes, multiplied on the 6-bit matrix pipe
+// =============================================================================================
+// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in the E3M2 format runs at twice the INT8 rate.
+// E3M2 represents every integer in [-8, 8] exactly, products are integers of magnitude <= 64 and
+// the fp32 accumulator stays exact below 2^24 (Kpad < 131072 is enforced), so the result equals the
+// integer GEMM bit for bit.  A lane's operand is 32 consecutive k-values = 24 bytes (6 VGPRs); lane l
+// holds row (l % 32), k-values 32 (l / 32) .. +31 of the 64-deep k-slice.
+//
+// Storage (written by the quantizer) is shaped by three facts measured on this chip:
+//   - blocked along k: block t holds, for every row in turn, the 96 bytes of its codes 128 t .. 128 t + 127
+//     (address (t * rows + row) * 96), so one k-stage of a tile operand is one contiguous run of 256 * 96
+//     bytes of whole cache lines.  Row-major rows make every 96-byte piece straddle 128-byte lines, which
+//     more than doubled the traffic between L2 and the compute units and capped the kernel there.
+//   - a 48-byte group (one k-slice of a row) is stored X_a Y_a Y_b X_b, X / Y = first 16 / last 8 bytes of
+//     a 32-code unit's bit stream: each lane finds its 24 bytes as one aligned 16-byte and one aligned
+//     8-byte piece, in register order, whichever k-half it serves (no selects).
+//   - (a, b) = (0, 1) in rows with bit 4 clear, (1, 0) otherwise.  LDS has 64 banks of 4 bytes; an 8-byte
+//     read serves 32 lanes per pass, and rows 16 apart (1536 bytes) share their banks: the exchange moves
+//     the 8-byte pieces of rows 16..31 of a fragment to the other half of the 16-byte bank pair.
+// In LDS rows stay 96 bytes apart, which repeats the bank alignment every 8 rows; rows with
+// (bit 2 ^ bit 3) set hold their two groups in swapped order (done by the copy: each lane of a direct
+// global->LDS copy fetches the 16-byte chunk that belongs at its LDS position).  Among the layouts of
+// this family, this pair of rules is one of those for which a probe kernel measured both reads at full
+// rate (4 cycles per 16-byte, 2.5 per 8-byte wave-read).
+//
+// gemm_f6_tile: tile 256 x 256, 8 waves (2 x 4), wave tile 128 x 64, the ping-pong schedule of
+// gemm_dma_tile with one phase per stage.  A stage is one block (two k-slices), 48 KiB in LDS, three
+// stages in a ring (the stage time is half the INT8 kernel's, so two stages are kept in flight).
+template <int BM, int BN>
+__device__ __forceinline__ void gemm_f6_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
+                                             const uint8_t* __restrict__ B, int M, int N, int rowbytes,
+                                             const float* __restrict__ s_x, const float* __restrict__ s_w,
+                                             void* __restrict__ Y, int y_dtype, int ldy,
+                                             const float* __restrict__ bias)
+{
+    constexpr int WM = 2, WN = 4, NW = 8, NSTAGE = 3;
+    constexpr int SB = 96;                          // stage bytes per row
+    constexpr int CPR = SB / 16;                    // 6 chunks per row
+    constexpr int STAGE = (BM + BN) * SB;
+    constexpr int A_BLOCKS = BM * CPR / 64 / NW;    // 1 KiB copy blocks per wave per stage
+    constexpr int B_BLOCKS = BN * CPR / 64 / NW;
+    constexpr int LPS = A_BLOCKS + B_BLOCKS;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int KS = 2;                           // 64-deep k-slices per stage
+    constexpr int VM_KEEP = (NSTAGE - 2) * LPS;
+    constexpr int WAIT_KEEP = (VM_KEEP & 0xf) | ((VM_KEEP >> 4) << 14) | 0x0f70;
+    constexpr int WAIT_ALL = 0x0f70;
+    static_assert((BM * CPR) % (64 * NW) == 0 && (BN * CPR) % (64 * NW) == 0, "copy blocks must tile the stage");
+    static_assert(VM_KEEP < 64, "stage count");
+    typedef v16f acc_t;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk = rowbytes / SB;                   // whole blocks only (Kpad is a multiple of 128)
+    const size_t blockA = (size_t)M * SB, blockB = (size_t)N * SB;
+
+    // ---- copy mapping: block b of an operand covers LDS chunks 64 b .. 64 b + 63 of its part of the
+    //      stage; chunk c sits in row c / 6 at position c % 6 and holds the global chunk of the same
+    //      row with the two 3-chunk groups swapped when bit 2 ^ bit 3 of the row is set ----
+    uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
+#pragma unroll
+    for (int j = 0; j < A_BLOCKS; ++j) {
+        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
+        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
+        offA[j] = (uint32_t)min(m0 + row, M - 1) * (uint32_t)SB + gc * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < B_BLOCKS; ++j) {
+        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
+        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
+        offB[j] = (uint32_t)min(n0 + row, N - 1) * (uint32_t)SB + gc * 16;
+    }
+    static_assert(A_BLOCKS == B_BLOCKS, "square tile");
+    const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
+    auto issue_any = [&](int stage_index) {
+        const uint32_t sA = lds0 + (stage_index % NSTAGE) * STAGE;
+        const uint32_t sB = sA + BM * SB;
+        const uint8_t* gA = A + stage_index * blockA;
+        const uint8_t* gB = B + stage_index * blockB;
+#pragma unroll
+        for (int j = 0; j < A_BLOCKS; ++j) dma16(gA, offA[j], sA + j * NW * 1024);
+#pragma unroll
+        for (int j = 0; j < B_BLOCKS; ++j) dma16(gB, offB[j], sB + j * NW * 1024);
+    };
+
+    // ---- operand read offsets.  A 48-byte group is stored X_a Y_a Y_b X_b (X: first 16, Y: last 8 bytes of
+    //      a 32-code unit's stream) with (a, b) = (0, 1) in rows with bit 4 clear, (1, 0) otherwise: the lane
+    //      of k-half h takes X at 0 / Y at 16 or X at 32 / Y at 24, both reads naturally aligned, and the 8-byte
+    //      reads of 32 consecutive rows fall into four different quarter-positions of the bank cycle ----
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int swp = ((frow >> 2) ^ (frow >> 3)) & 1;
+    const int mirrored = (fhalf ^ (frow >> 4)) & 1;
+    const int a_rd = (wm * TM + frow) * SB, b_rd = BM * SB + (wn * TN + frow) * SB;
+    int xofs[KS], yofs[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        xofs[ks] = 48 * (ks ^ swp) + (mirrored ? 32 : 0);
+        yofs[ks] = 48 * (ks ^ swp) + (mirrored ? 24 : 16);
+    }
+    auto read24 = [&](const uint8_t* p, int ks) -> v8i {
+        const v4i x = *reinterpret_cast<const v4i*>(p + xofs[ks]);
+        const v2i y = *reinterpret_cast<const v2i*>(p + yofs[ks]);
+        return v8i{x[0], x[1], x[2], x[3], y[0], y[1], 0, 0};
+    };
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // ---- ping-pong over the stages: see gemm_dma_tile for the barrier bookkeeping (NPH = 1) ----
+    const bool group_b = wave >= 4;
+    v8i pa[KS][FM], pb[KS][FN];
+#pragma unroll
+    for (int st = 0; st < NSTAGE - 1; ++st)
+        if (st < nk) issue_any(st);
+    if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    __builtin_amdgcn_s_barrier();
+    if (group_b) __builtin_amdgcn_s_barrier();
+    int buf = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* s = smem + buf * STAGE;
+        buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
+        const bool steady = kt + NSTAGE - 1 < nk;
+        // ---------------- memory phase ----------------
+        if (steady) issue_any(kt + NSTAGE - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) pa[ks][i] = read24(s + a_rd + i * 32 * SB, ks);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) pb[ks][j] = read24(s + b_rd + j * 32 * SB, ks);
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);                                 // lgkmcnt(0)
+        if (group_b) {                                                      // B: my copy of stage kt+1 landed
+            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // ---------------- compute phase ----------------
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pb[ks][j], pa[ks][i], acc[i][j], 3, 3, 0, 127, 0, 127);
+        __builtin_amdgcn_s_setprio(0);
+        if (!group_b) {                                                     // A: my copy of stage kt+1 landed
+            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!group_b) __builtin_amdgcn_s_barrier();
+
+    store_tile<MODE_F6, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                                smem + wave * (TM * TN * 2), bias);
+}
+
+// The same product with four waves (2 x 2) and wave tiles of 128 x 128: every operand fetched from LDS
+// feeds four MFMAs instead of two or four, which takes the LDS reads from 3/4 to 1/2 of an operand per
+// MFMA -- the ping-pong kernel above is bound by them.  One wave per SIMD: the LDS reads of the next
+// k-slice and their selects are issued between the MFMAs of the current one (operands double-buffered
+// in registers).  Three stage buffers; the barrier sits in the middle of a stage, after the reads of
+// its second slice: it publishes stage kt+1 (each wave waited for its own copies), frees stage kt's
+// buffer for the copy of stage kt+3, and lets the MFMAs of the second slice overlap the first reads
+// of stage kt+1.
+template <int BM, int BN>
+__device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
+                                                  const uint8_t* __restrict__ B, int M, int N, int rowbytes,
+                                                  const float* __restrict__ s_x, const float* __restrict__ s_w,
+                                                  void* __restrict__ Y, int y_dtype, int ldy,
+                                                  const float* __restrict__ bias)
+{
+    constexpr int WM = 2, WN = 2, NW = 4, NSTAGE = 3;
+    constexpr int SB = 96, CPR = SB / 16;
+    constexpr int STAGE = (BM + BN) * SB;
+    constexpr int A_BLOCKS = BM * CPR / 64 / NW, B_BLOCKS = BN * CPR / 64 / NW;
+    constexpr int LPS = A_BLOCKS + B_BLOCKS;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int NR = FM + FN;                      // operands of one k-slice
+    constexpr int NM = FM * FN;                      // MFMAs of one k-slice
+    constexpr int WAIT_ONE = (LPS & 0xf) | ((LPS >> 4) << 14) | 0x0f70;          // vmcnt(LPS): one stage may be in flight
+    constexpr int WAIT_TWO = ((2 * LPS) & 0xf) | (((2 * LPS) >> 4) << 14) | 0x0f70;
+    constexpr int WAIT_ALL = 0x0f70;
+    static_assert((BM * CPR) % (64 * NW) == 0 && (BN * CPR) % (64 * NW) == 0, "copy blocks must tile the stage");
+    static_assert(2 * LPS < 64 && NR <= NM, "pipeline shape");
+    typedef v16f acc_t;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk = rowbytes / SB;
+    const size_t blockA = (size_t)M * SB, blockB = (size_t)N * SB;
+
+    uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
+#pragma unroll
+    for (int j = 0; j < A_BLOCKS; ++j) {
+        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
+        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
+        offA[j] = (uint32_t)min(m0 + row, M - 1) * (uint32_t)SB + gc * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < B_BLOCKS; ++j) {
+        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
+        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
+        offB[j] = (uint32_t)min(n0 + row, N - 1) * (uint32_t)SB + gc * 16;
+    }
+    const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
+    auto issue_any = [&](int stage_index) {
+        const uint32_t sA = lds0 + (stage_index % NSTAGE) * STAGE;
+        const uint32_t sB = sA + BM * SB;
+        const uint8_t* gA = A + stage_index * blockA;
+        const uint8_t* gB = B + stage_index * blockB;
+#pragma unroll
+        for (int j = 0; j < A_BLOCKS; ++j) dma16(gA, offA[j], sA + j * NW * 1024);
+#pragma unroll
+        for (int j = 0; j < B_BLOCKS; ++j) dma16(gB, offB[j], sB + j * NW * 1024);
+    };
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int swp = ((frow >> 2) ^ (frow >> 3)) & 1;
+    const int mirrored = (fhalf ^ (frow >> 4)) & 1;      // see gemm_f6_tile
+    const int a_rd = (wm * TM + frow) * SB, b_rd = BM * SB + (wn * TN + frow) * SB;
+    int xofs[2], yofs[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        xofs[ks] = 48 * (ks ^ swp) + (mirrored ? 32 : 0);
+        yofs[ks] = 48 * (ks ^ swp) + (mirrored ? 24 : 16);
+    }
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // operands of a k-slice in the order the MFMA walk (i outer, j inner) first needs them: a0, b0..b3, a1..a3
+    v8i opa[2][FM], opb[2][FN];
+    auto op_addr = [&](const uint8_t* st, int r) -> const uint8_t* {
+        return (r == 0) ? st + a_rd : (r <= FN ? st + b_rd + (r - 1) * 32 * SB : st + a_rd + (r - FN) * 32 * SB);
+    };
+    auto read_op = [&](const uint8_t* st, int ks, int buf, int r) {
+        const uint8_t* p = op_addr(st, r);
+        const v4i x = *reinterpret_cast<const v4i*>(p + xofs[ks]);
+        const v2i y = *reinterpret_cast<const v2i*>(p + yofs[ks]);
+        const v8i o = {x[0], x[1], x[2], x[3], y[0], y[1], 0, 0};
+        if (r == 0) opa[buf][0] = o;
+        else if (r <= FN) opb[buf][r - 1] = o;
+        else opa[buf][r - FN] = o;
+    };
+    // the MFMAs of the slice held in buffer `cur`; when `rd`, the operands of slice `rks` of stage `rs` are
+    // read into the other buffer in their shadow
+    auto slice = [&](int cur, const uint8_t* rs, int rks, auto rd_tag) {
+        constexpr bool rd = decltype(rd_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NM; ++t) {
+            const int i = t / FN, j = t % FN;
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(opb[cur][j], opa[cur][i], acc[i][j], 3, 3, 0, 127, 0, 127);
+            if constexpr (rd) {
+                if (t < NR) read_op(rs, rks, cur ^ 1, t);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+#pragma unroll
+    for (int st = 0; st < NSTAGE; ++st)
+        if (st < nk) issue_any(st);
+    if (nk >= 3) __builtin_amdgcn_s_waitcnt(WAIT_TWO);
+    else if (nk == 2) __builtin_amdgcn_s_waitcnt(WAIT_ONE);
+    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) read_op(smem, 0, 0, r);
+    __builtin_amdgcn_sched_barrier(0);
+
+    int buf = 0;
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        const uint8_t* s = smem + buf * STAGE;
+        buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
+        const uint8_t* sn = smem + buf * STAGE;
+        slice(0, s, 1, std::true_type{});           // slice 0; reads slice 1 of this stage
+        // slice 1 of stage kt is in registers: its buffer is free, and stage kt+1 must be complete
+        if (kt + 2 < nk) __builtin_amdgcn_s_waitcnt(WAIT_ONE & 0xc07f);     // + lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(WAIT_ALL & 0xc07f);
+        __syncthreads();
+        if (kt + NSTAGE < nk) issue_any(kt + NSTAGE);
+        __builtin_amdgcn_sched_barrier(0);
+        slice(1, sn, 0, std::true_type{});          // slice 1; reads slice 0 of the next stage
+    }
+    {   // last stage: nothing further to read
+        const uint8_t* s = smem + buf * STAGE;
+        slice(0, s, 1, std::true_type{});
+        slice(1, s, 0, std::false_type{});
+    }
+    __syncthreads();                                // every wave is past its last LDS operand read
+
+    store_tile<MODE_F6, FM, FN, 2>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                                   smem + wave * (64 * TN * 2), bias);
+}
+
+__global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B,
+                                                           int M, int N, int rowbytes, const float* __restrict__ s_x,
+                                                           const float* __restrict__ s_w, void* __restrict__ Y,
+                                                           int y_dtype, int ldy, int tiles_m, int tiles_n, Batch bt)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    A += (size_t)blockIdx.y * bt.stride_a;
+    B += (size_t)blockIdx.y * bt.stride_b;
+    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    gemm_f6_wide_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt.bias);
+}
+
+__global__ __launch_bounds__(512) void gemm_f6_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, int M,
+                                                      int N, int rowbytes, const float* __restrict__ s_x,
+                                                      const float* __restrict__ s_w, void* __restrict__ Y, int y_dtype,
+                                                      int ldy, int tiles_m, int tiles_n, Batch bt)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    A += (size_t)blockIdx.y * bt.stride_a;
+    B += (size_t)blockIdx.y * bt.stride_b;
+    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    gemm_f6_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt.bias);
+}
+
+// =============================================================================================
 // gemm_reg_kernel: global -> registers -> LDS
 // =============================================================================================
 template <int MODE, int BM, int BN, int BKB, int WM, int WN>
@@ -982,12 +1329,40 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
 
 }  // namespace
 
-// This file is compiled once per operand mode (FQ_GEMM_MODE = 0 INT8, 1 packed INT4, 2 bf16), each
+// This file is compiled once per operand mode (FQ_GEMM_MODE = 0 INT8, 1 packed INT4, 2 bf16, 3 E3M2), each
 // translation unit holding that mode's kernels and exporting its dispatcher.
 #ifndef FQ_GEMM_MODE
-#error "compile with -DFQ_GEMM_MODE=0, 1 or 2"
+#error "compile with -DFQ_GEMM_MODE=0, 1, 2 or 3"
 #endif
-#if FQ_GEMM_MODE == 0
+#if FQ_GEMM_MODE == 3
+int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                     void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
+{
+    if (bt.count < 1 || bt.count > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", bt.count);
+    if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
+        return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
+    if (rowbytes % 96) return fail(FQ_ERR_SHAPE, "E3M2 rows must be whole 96-byte blocks");
+    constexpr int smem = 3 * 512 * 96;
+    static bool attr_set = false;
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_kernel), smem, attr_set)) return rc;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const long long tiles = (long long)tiles_m * tiles_n;
+    if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
+    static bool attr_set_wide = false;
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel), smem, attr_set_wide)) return rc;
+    if (forced_gemm_variant() != 0)
+        gemm_f6_wide_kernel<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(256), smem, stream>>>(
+            static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+            tiles_m, tiles_n, bt);
+    else
+        gemm_f6_kernel<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(512), smem, stream>>>(
+            static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+            tiles_m, tiles_n, bt);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
+}
+#elif FQ_GEMM_MODE == 0
 int gemm_dispatch_i8(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                      void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {

@@ -1,5 +1,5 @@
 // Kernel-variant selection and the entry points of the GEMM family: they forward to the per-mode
-// dispatchers, which live in the three translation units built from fq_gemm.hip.
+// dispatchers, which live in the four translation units built from fq_gemm.hip.
 #include "fq_internal.h"
 
 namespace fq {
@@ -24,6 +24,7 @@ int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int 
 {
     const Batch one = {1, 0, 0, 0, bias};
     if (bits == 8) return gemm_dispatch_i8(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, one, stream);
+    if (bits == FQ_BITS_I4_E3M2) return gemm_dispatch_f6(Xq, Wq, M, N, Kpad / 4 * 3, s_x, s_w, Y, y_dtype, ldy, one, stream);
     return gemm_dispatch_i4(Xq, Wq, M, N, Kpad / 2, s_x, s_w, Y, y_dtype, ldy, one, stream);
 }
 

@@ -64,6 +64,8 @@ int gemm_dispatch_i4(const void* A, const void* B, int M, int N, int rowbytes, c
                      void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
 int gemm_dispatch_bf16(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                        void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
+int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
+                       void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
 int forced_gemm_variant();   // -1 = choose from the shape
 int set_gemm_variant(int v);
 

@@ -27,6 +27,30 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+// 12 bytes at 4-byte alignment (a 3-element vector type would claim 16)
+struct __attribute__((aligned(4))) u3 { uint32_t a, b, c; };
+
+// 6-bit E3M2 code (sign, 3 exponent bits with bias 3, 2 mantissa bits) of an integer q in [-8, 8]: the
+// fp32 form of |q| already holds the exponent and, in its top mantissa bits, the two mantissa bits.
+__device__ __forceinline__ uint32_t e3m2_code(int q)
+{
+    const int a = q < 0 ? -q : q;
+    const uint32_t mag = a ? (__float_as_uint((float)a) >> 21) - ((127u - 3u) << 2) : 0u;
+    return (q < 0 ? 0x20u : 0u) | mag;
+}
+// 16 codes as a 96-bit little-endian bit stream
+__device__ __forceinline__ u3 pack16_e3m2(const int (&q)[16])
+{
+    unsigned long long lo = 0, hi = 0;       // lo: slots 0..9 (60 bits) + 4 bits of slot 10; hi: the rest
+#pragma unroll
+    for (int i = 0; i < 10; ++i) lo |= (unsigned long long)e3m2_code(q[i]) << (6 * i);
+    const unsigned long long c10 = e3m2_code(q[10]);
+    lo |= c10 << 60;
+    hi = c10 >> 4;
+#pragma unroll
+    for (int i = 11; i < 16; ++i) hi |= (unsigned long long)e3m2_code(q[i]) << (6 * i - 64);
+    return u3{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi};
+}
 
 template <int DT> struct Elem;
 template <> struct Elem<FQ_F32> {
@@ -328,10 +352,12 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
 // ---------------------------------------------------------------------------------------------
 // flatten + quantize
 // ---------------------------------------------------------------------------------------------
+// BITS = 8, 4, or 6 = the 4-bit quantizer with its values stored as 6-bit E3M2 codes (k-blocked layout)
 template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
 {
-    constexpr float hi = (float)((1 << (BITS - 1)) - 1);
-    constexpr float lo = -(float)(1 << (BITS - 1));
+    constexpr int QB = (BITS == 6) ? 4 : BITS;
+    constexpr float hi = (float)((1 << (QB - 1)) - 1);
+    constexpr float lo = -(float)(1 << (QB - 1));
     float r = rintf(x * m);                 // one fp32 multiply, then round-half-even
     r = fminf(fmaxf(r, lo), hi);
     return (int)r;
@@ -472,7 +498,11 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
     const int r0 = blockIdx.x * R;
     const int nthr = blockDim.x;
     const int nr = min(M - r0, R);
-    const size_t orow_bytes = (BITS == 8) ? (size_t)Kpad : (size_t)(Kpad >> 1);
+    // bytes of an output row and of one group of 16 slots: 16 (INT8), 8 (INT4 nibbles), 12 (E3M2 codes)
+    constexpr int GB = (BITS == 8) ? 16 : (BITS == 4 ? 8 : 12);
+    // INT8 / INT4 rows are dense (E3M2 output has its own addressing, see store_e3m2)
+    const size_t orow_bytes = (size_t)(Kpad >> 4) * GB;
+    auto group_ofs = [&](int g) -> size_t { return (size_t)g * GB; };
 
     // sources of the phase-2 slots as 16-bit channel numbers (0xffff: the slot holds 0); eight slots per
     // thread and pass, loaded before any is stored, so that the passes do not each wait a round trip
@@ -499,6 +529,8 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
                 w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
                        ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
             *reinterpret_cast<v4u*>(o) = w;
+        } else if (BITS == 6) {
+            (void)o;                                // E3M2 output goes through store_e3m2
         } else {
             v2u w;
 #pragma unroll
@@ -509,6 +541,25 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
                 w[i] = acc;
             }
             *reinterpret_cast<v2u*>(o) = w;
+        }
+    };
+    // E3M2 output, blocked along k: block t (codes 128 t .. 128 t + 127) holds 96 bytes of every row in turn.
+    // A row's 96 bytes are two 48-byte groups of 64 codes; the 24-byte bit stream of each 32-code unit a is
+    // split into its first 16 bytes X_a and last 8 bytes Y_a, and the group is stored X_a Y_a Y_b X_b with
+    // (a, b) = (0, 1) in rows whose index has bit 4 clear and (1, 0) in the others (what the GEMM's LDS reads
+    // want).  A thread's 16 codes are half a unit: stream bytes 0..11 (e = 0) or 12..23 (e = 1).
+    auto store_e3m2 = [&](const int (&q)[16], int row, int g) {
+        const u3 v = pack16_e3m2(q);
+        const int gi = g & 7, e = gi & 1;
+        uint8_t* grp = out + ((size_t)(g >> 3) * (size_t)M + (size_t)row) * 96 + 48 * (gi >> 2);
+        const bool mirrored = (((gi >> 1) ^ (row >> 4)) & 1) != 0;
+        if (!mirrored) {
+            *reinterpret_cast<u3*>(grp + 12 * e) = v;                 // X at 0, Y at 16: the plain stream
+        } else if (e == 0) {
+            *reinterpret_cast<u3*>(grp + 32) = v;                     // X at 32
+        } else {
+            *reinterpret_cast<uint32_t*>(grp + 44) = v.a;             // the last 4 bytes of X
+            *reinterpret_cast<v2u*>(grp + 24) = v2u{v.b, v.c};        // Y at 24
         }
     };
     // the general form of one group over rows [ra, rb) of the strip: every slot's source element is
@@ -530,13 +581,14 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
             ident[i] = to_lds && s[i] == p0 + i;
             if ((unsigned)s[i] >= (unsigned)K) { s[i] = 0; m[i] = 0.0f; }
         }
-        uint8_t* o = out + (size_t)(r0 + ra) * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
+        uint8_t* o = out + (size_t)(r0 + ra) * orow_bytes + group_ofs(g);
         const T* row = X + (size_t)(r0 + ra) * ld;
         for (int r = ra; r < rb; ++r, row += ld, o += orow_bytes) {
             int q[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(Elem<DT>::widen(row[s[i]]), m[i]);
-            pack_store(q, o);
+            if constexpr (BITS == 6) store_e3m2(q, r0 + r, g);
+            else pack_store(q, o);
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 if (ident[i]) qs[(size_t)r * KQ + p0 + i] = (uint8_t)q[i];
@@ -557,7 +609,7 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
 #pragma unroll
             for (int j = 0; j < 4; ++j) m[4 * i + j] = mv[j];
         }
-        uint8_t* o = out + (size_t)r0 * orow_bytes + ((BITS == 8) ? p0 : (p0 >> 1));
+        uint8_t* o = out + (size_t)r0 * orow_bytes + group_ofs(g);
         const T* row = X + (size_t)r0 * ld + p0;
         uint8_t* ql = qs + p0;
 #pragma unroll 4
@@ -569,7 +621,8 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
             int q[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) q[i] = quant1<BITS>(x[i], m[i]);
-            pack_store(q, o);
+            if constexpr (BITS == 6) store_e3m2(q, r0 + r, g);
+            else pack_store(q, o);
             v4u w;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -619,7 +672,8 @@ __global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __r
         for (int u = 0; u < U; ++u)
             if (ok[u]) {
                 const int g = NH + gt[u];
-                pack_store(q[u], out + (size_t)(r0 + rr[u]) * orow_bytes + ((BITS == 8) ? (g << 4) : (g << 3)));
+                if constexpr (BITS == 6) store_e3m2(q[u], r0 + rr[u], g);
+                else pack_store(q[u], out + (size_t)(r0 + rr[u]) * orow_bytes + group_ofs(g));
             }
     }
 }
@@ -655,8 +709,15 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
                      int Kpad, int bits, int mode, const float* absmax_in, float T, void* out, float* scale_out,
                      const ActWorkspace& ws, hipStream_t stream)
 {
-    const int qmax = (1 << (bits - 1)) - 1;
+    const int qmax = (bits == 6) ? 7 : (1 << (bits - 1)) - 1;       // 6: the 4-bit quantizer, E3M2 storage
     const bool peel = mode >= 3;
+    if (bits == 6) {
+        // E3M2 storage exists in the row-strip kernel only: refuse before anything is enqueued
+        const size_t kq1 = (size_t)(K & ~15), tail1 = 2 * ((size_t)Kpad - kq1) + ((size_t)Kpad - kq1) / 16;
+        if (peel || K < 16 || kq1 + tail1 > 64u * 1024u)
+            return fail(FQ_ERR_DTYPE, "E3M2 storage (bits = 6) needs K >= 16 and a layer narrow enough for the "
+                                      "row-strip kernel, and is not available for the peel split");
+    }
     if (mode != 1 && mode != 4) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, T,
                                                             ws.mslot, scale_out, ws.scalars, ws.gflag);
@@ -675,6 +736,8 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
             const int nthr = 256;
             if (bits == 8)
                 flatten_quant_rows_kernel<DT, 8><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+            else if (bits == 6)
+                flatten_quant_rows_kernel<DT, 6><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
             else
                 flatten_quant_rows_kernel<DT, 4><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
             hipError_t e = hipGetLastError();

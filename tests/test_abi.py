@@ -124,6 +124,15 @@ def test_device_calls_validate_before_launching():
     assert L.fq_gemm_select(-1) == 0
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 8) >= 8 * 64 + ws
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 4) >= 8 * 32 + ws
+    # E3M2 storage of the 4-bit layer: Kpad a multiple of 128 (whole blocks), 3 bytes per 4 slots
+    e3 = fq.binding.FQ_BITS_I4_E3M2
+    assert L.fq_gemm_i4_e3m2(dummy, dummy, 4, 4, 96, dummy, dummy, None, dummy, fq.FQ_F32, 4, None) == 2
+    assert b"multiple of 128" in L.fq_last_error_string()
+    assert L.fq_gemm_i4_e3m2(dummy, None, 4, 4, 128, dummy, dummy, None, dummy, fq.FQ_F32, 4, None) == 1
+    assert L.fq_gemm_i4_e3m2(dummy, dummy, 4, 4, 128, dummy, dummy, dummy, dummy, fq.FQ_I32, 4, None) == 3   # bias + raw
+    args96 = (dummy, fq.FQ_BF16, 4, 64, 64, dummy, dummy, 96, e3, None, dummy, dummy, dummy, 1 << 20, None)
+    assert L.fq_flatten_quant_act(*args96) == 2
+    assert fq.fq_linear_workspace_bytes(8, 64, 128, e3) >= 8 * 96 + fq.fq_act_workspace_bytes(64, 128)
 
 
 @pytest.mark.parametrize("seed", range(4))
