@@ -996,6 +996,13 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
         for (int j = 0; j < B_BLOCKS; ++j) dma16(gB, offB[j], sB + j * NW * 1024);
     };
 
+    // copy instruction `idx` (0 .. LPS-1) of a stage: the A blocks, then the B blocks
+    auto issue_one = [&](int stage_index, int idx) {
+        const uint32_t sA = lds0 + (stage_index % NSTAGE) * STAGE;
+        if (idx < A_BLOCKS) dma16(A + stage_index * blockA, offA[idx], sA + idx * NW * 1024);
+        else dma16(B + stage_index * blockB, offB[idx - A_BLOCKS], sA + BM * SB + (idx - A_BLOCKS) * NW * 1024);
+    };
+
     const int frow = lane & 31, fhalf = lane >> 5;
     const int swp = ((frow >> 2) ^ (frow >> 3)) & 1;
     const int mirrored = (fhalf ^ (frow >> 4)) & 1;      // see gemm_f6_tile
@@ -1020,25 +1027,42 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
     auto op_addr = [&](const uint8_t* st, int r) -> const uint8_t* {
         return (r == 0) ? st + a_rd : (r <= FN ? st + b_rd + (r - 1) * 32 * SB : st + a_rd + (r - FN) * 32 * SB);
     };
-    auto read_op = [&](const uint8_t* st, int ks, int buf, int r) {
-        const uint8_t* p = op_addr(st, r);
-        const v4i x = *reinterpret_cast<const v4i*>(p + xofs[ks]);
-        const v2i y = *reinterpret_cast<const v2i*>(p + yofs[ks]);
-        const v8i o = {x[0], x[1], x[2], x[3], y[0], y[1], 0, 0};
-        if (r == 0) opa[buf][0] = o;
-        else if (r <= FN) opb[buf][r - 1] = o;
-        else opa[buf][r - FN] = o;
+    // operand r of a slice, read in two steps (the 16-byte piece, then the 8-byte piece)
+    auto set_op = [&](int buf, int r) -> v8i& {
+        return (r == 0) ? opa[buf][0] : (r <= FN ? opb[buf][r - 1] : opa[buf][r - FN]);
     };
-    // the MFMAs of the slice held in buffer `cur`; when `rd`, the operands of slice `rks` of stage `rs` are
-    // read into the other buffer in their shadow
-    auto slice = [&](int cur, const uint8_t* rs, int rks, auto rd_tag) {
+    auto read_x = [&](const uint8_t* st, int ks, int buf, int r) {
+        const v4i x = *reinterpret_cast<const v4i*>(op_addr(st, r) + xofs[ks]);
+        v8i& o = set_op(buf, r);
+        o[0] = x[0]; o[1] = x[1]; o[2] = x[2]; o[3] = x[3];
+    };
+    auto read_y = [&](const uint8_t* st, int ks, int buf, int r) {
+        const v2i y = *reinterpret_cast<const v2i*>(op_addr(st, r) + yofs[ks]);
+        v8i& o = set_op(buf, r);
+        o[4] = y[0]; o[5] = y[1]; o[6] = 0; o[7] = 0;
+    };
+    auto read_op = [&](const uint8_t* st, int ks, int buf, int r) {
+        read_x(st, ks, buf, r);
+        read_y(st, ks, buf, r);
+    };
+    // `copy_stage` >= 0: the copy instructions of that stage are issued one per MFMA, after the reads
+    auto slice = [&](int cur, const uint8_t* rs, int rks, auto rd_tag, auto copy_tag, int copy_stage) {
         constexpr bool rd = decltype(rd_tag)::value;
+        constexpr bool cp = decltype(copy_tag)::value;
+        static_assert(LPS <= NM, "one copy per MFMA slot");
 #pragma unroll
         for (int t = 0; t < NM; ++t) {
             const int i = t / FN, j = t % FN;
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(opb[cur][j], opa[cur][i], acc[i][j], 3, 3, 0, 127, 0, 127);
             if constexpr (rd) {
-                if (t < NR) read_op(rs, rks, cur ^ 1, t);
+                // one LDS read per MFMA: operand t/2 of the next slice (its first MFMA needs operands 0
+                // and 1, MFMA j operand 1 + j, MFMA 4 i operand 4 + i: all read at least one slice earlier)
+                static_assert(NM == 2 * NR, "one LDS read per MFMA slot");
+                if (t & 1) read_y(rs, rks, cur ^ 1, t >> 1);
+                else read_x(rs, rks, cur ^ 1, t >> 1);
+            }
+            if constexpr (cp) {
+                if (t >= NM - LPS) issue_one(copy_stage, t - (NM - LPS));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1055,24 +1079,29 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
     for (int r = 0; r < NR; ++r) read_op(smem, 0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
 
+    typedef std::true_type yes;
+    typedef std::false_type no;
     int buf = 0;
-    for (int kt = 0; kt + 1 < nk; ++kt) {
+    // one stage: slice 0 (reads slice 1 of the stage), the barrier, slice 1 (reads slice 0 of the next
+    // stage and, when `copy_tag`, copies stage kt+3 into the buffer the barrier freed)
+    auto stage = [&](int kt, auto copy_tag) {
         const uint8_t* s = smem + buf * STAGE;
         buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
         const uint8_t* sn = smem + buf * STAGE;
-        slice(0, s, 1, std::true_type{});           // slice 0; reads slice 1 of this stage
+        slice(0, s, 1, yes{}, no{}, 0);
         // slice 1 of stage kt is in registers: its buffer is free, and stage kt+1 must be complete
         if (kt + 2 < nk) __builtin_amdgcn_s_waitcnt(WAIT_ONE & 0xc07f);     // + lgkmcnt(0)
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL & 0xc07f);
         __syncthreads();
-        if (kt + NSTAGE < nk) issue_any(kt + NSTAGE);
-        __builtin_amdgcn_sched_barrier(0);
-        slice(1, sn, 0, std::true_type{});          // slice 1; reads slice 0 of the next stage
-    }
+        slice(1, sn, 0, yes{}, copy_tag, kt + NSTAGE);
+    };
+    int kt = 0;
+    for (; kt + NSTAGE < nk; ++kt) stage(kt, yes{});
+    for (; kt + 1 < nk; ++kt) stage(kt, no{});
     {   // last stage: nothing further to read
         const uint8_t* s = smem + buf * STAGE;
-        slice(0, s, 1, std::true_type{});
-        slice(1, s, 0, std::false_type{});
+        slice(0, s, 1, yes{}, no{}, 0);
+        slice(1, s, 0, no{}, no{}, 0);
     }
     __syncthreads();                                // every wave is past its last LDS operand read
 
