@@ -4,11 +4,15 @@
 Workload (default): the metric's "M = 8192 LLaMA-7B shapes" — the INT4 FFN pair 4096->11008 and
 11008->4096 plus the INT8 4096->4096 projection, all at M = 8192 tokens, synthetic outlier-bearing
 bf16 activations (fq_workloads.py).  One step = one fq_linear call per layer: dynamic per-tensor
-absmax, fused flatten-quantize, integer MFMA GEMM with the dequantize epilogue (bf16 out).
+absmax, fused flatten-quantize, integer GEMM with the dequantize epilogue (bf16 out).
 Inputs are resident in HBM before the timed region.
 
+The 4-bit layers run in E3M2 storage on the 6-bit matrix pipe by default (same quantized integers and
+bit-identical accumulators, twice the int8 MFMA rate); --nibble runs them as packed nibbles on the int8
+MFMA.  Whichever is not the timed path is measured beside it and reported in the same line.
+
 Prints ONE JSON line: whole-step throughput in TOPS (integer ops actually executed,
-2*M*Kpad*N per layer), the roofline of the dominant kernel (the INT4 GEMM) from HIP-event timings
+2*M*Kpad*N per layer), the roofline of the dominant kernel (the 4-bit GEMM) from HIP-event timings
 taken in this process, and the CPU oracle timed on a bounded sample.
 """
 import argparse
@@ -24,9 +28,10 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of the dominant kernel (INT4 GEMM, average of its two launches per step) for
 # the default workload and kernel choice, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
 # by a plain 1 GiB copy in the same runs: profiles/pmc_traffic_bench_cfg3_m8192.txt.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0): 5.56e8}
+MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0, "nibble"): 5.56e8}
 
-INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (INT4 is widened to int8 on chip: same ceiling)
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (packed INT4 is widened to int8 on chip: same ceiling)
+FP6_PEAK_TFLOPS = 10100.0    # dense 6-bit MFMA peak: the ceiling of the 4-bit layers in E3M2 storage
 BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
@@ -69,6 +74,9 @@ def main():
                     help="also run one plain 1 GiB device copy (the reference kernel for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-bmm", action="store_true", help="skip the attention-shaped batched-product rows")
+    ap.add_argument("--nibble", action="store_true",
+                    help="time the 4-bit layers as packed nibbles on the int8 MFMA instead of E3M2 codes on the 6-bit MFMA")
+    ap.add_argument("--no-alt", action="store_true", help="do not also measure the 4-bit storage that is not timed")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1")
@@ -83,6 +91,11 @@ def main():
     fq.lib()
     dev = "cuda:0"
     fq.fq_gemm_select(args.variant)
+    E3 = fq.binding.FQ_BITS_I4_E3M2
+    path = "nibble" if args.nibble else "e3m2"
+    # storage of a layer's quantized tensors on the timed path / on the other path (None: no other)
+    store_of = lambda bits: bits if (bits == 8 or args.nibble) else E3
+    alt_of = lambda bits: None if (bits == 8 or args.no_alt) else (E3 if args.nibble else 4)
 
     # ---------------- build the layers (offline part: plan + weight quantization) ----------------
     layers = []
@@ -97,7 +110,11 @@ def main():
                     return torch.from_numpy(store.view(np.int16)).to(dev).view(torch.bfloat16)
                 return torch.from_numpy(store).to(dev)
             Xd, Wd = upload(L.X_store, sp.x_dtype), upload(L.W_store, sp.w_dtype)
-            lay = fq.FqLinear(Wd, L.chmax, L.T, sp.bits, device=dev, align=args.align)
+            lay = fq.FqLinear(Wd, L.chmax, L.T, store_of(sp.bits), device=dev, align=args.align)
+            lay_alt = None
+            if alt_of(sp.bits) is not None:
+                lay_alt = fq.FqLinear(Wd, L.chmax, L.T, alt_of(sp.bits), device=dev, align=args.align)
+                lay_alt.workspace(sp.M)
             Y = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             Ybf = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
             a_static = torch.tensor([L.T], dtype=torch.float32, device=dev) if args.static else None
@@ -105,8 +122,8 @@ def main():
             # operands of the bf16 baseline GEMM (the tensors themselves when they already are bf16)
             Xb = Xd if Xd.dtype == torch.bfloat16 else Xd.to(torch.bfloat16)
             Wb = Wd if Wd.dtype == torch.bfloat16 else Wd.to(torch.bfloat16)
-            layers.append(dict(name=f"{cname}.{sp.name}", spec=sp, L=L, X=Xd, W=Wd, Xb=Xb, Wb=Wb, lay=lay, Y=Y, Ybf=Ybf,
-                               a_static=a_static))
+            layers.append(dict(name=f"{cname}.{sp.name}", spec=sp, L=L, X=Xd, W=Wd, Xb=Xb, Wb=Wb, lay=lay, lay_alt=lay_alt,
+                               Y=Y, Ybf=Ybf, a_static=a_static))
             log(f"[setup] {cname}.{sp.name}: M={sp.M} K={sp.K} N={sp.N} bits={sp.bits} T={L.T:.4g} "
                 f"Kprime={lay.Kprime} Kpad={lay.Kpad} (+{100.0 * (lay.Kpad - sp.K) / sp.K:.1f}%) "
                 f"max n={int(lay.rep_host.max())} [{time.time() - t0:.1f}s]")
@@ -138,6 +155,21 @@ def main():
     torch.cuda.synchronize()
     t_step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # the same step with the 4-bit layers in the other storage (reported beside the timed path)
+    t_alt_ms = None
+    if any(d["lay_alt"] is not None for d in layers):
+        def step_alt():
+            for d in layers:
+                (d["lay_alt"] or d["lay"]).forward(d["X"], Y=d["Y"], absmax_in=d["a_static"])
+        for _ in range(args.warmup):
+            step_alt()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_alt()
+        torch.cuda.synchronize()
+        t_alt_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
     ops_hw = sum(2.0 * d["spec"].M * d["lay"].Kpad * d["spec"].N for d in layers)
     ops_eff = sum(2.0 * d["spec"].M * d["spec"].K * d["spec"].N for d in layers)
     value = ops_hw / (t_step_ms * 1e-3) / 1e12
@@ -149,16 +181,28 @@ def main():
     dom = dict(flops=0.0, ms=0.0, launches=0)       # the dominant kernel: INT4 GEMM (else INT8)
     dom_bits = 4 if any(d["spec"].bits == 4 for d in layers) else 8
     fqa = dict(bytes=0.0, ms=0.0)
+    def kernels_of(d, lay):
+        """(flatten-quantize call, GEMM call, bytes of Xq) of one layer in the storage of `lay`."""
+        sp, Kpad, st = d["spec"], lay.Kpad, lay.bits
+        if st == E3:
+            Xq = torch.empty((Kpad // 128, sp.M, 96), dtype=torch.uint8, device=dev)
+        else:
+            Xq = torch.empty((sp.M, Kpad if st == 8 else Kpad // 2), dtype=torch.int8 if st == 8 else torch.uint8, device=dev)
+        s_x = torch.empty(1, dtype=torch.float32, device=dev)
+        ws = torch.empty(fq.fq_act_workspace_bytes(sp.K, Kpad), dtype=torch.uint8, device=dev)
+        f_act = lambda: fq.fq_flatten_quant_act(d["X"], lay.src, lay.rep, st, Xq, s_x, ws, absmax_in=d["a_static"])
+        if st == E3:
+            f_gemm = lambda: fq.fq_gemm_i4_e3m2(Xq, lay.Wq, s_x, lay.s_w, None, d["Y"])
+        else:
+            gemm = fq.fq_gemm_i8 if st == 8 else fq.fq_gemm_i4
+            f_gemm = lambda: gemm(Xq, lay.Wq, s_x, lay.s_w, d["Y"])
+        return f_act, f_gemm, Xq.numel(), (Xq, s_x, ws)
+
+    alt = dict(flops=0.0, ms=0.0, launches=0)
     for d in layers:
         sp, lay = d["spec"], d["lay"]
         Kpad = lay.Kpad
-        cols = Kpad if sp.bits == 8 else Kpad // 2
-        Xq = torch.empty((sp.M, cols), dtype=torch.int8 if sp.bits == 8 else torch.uint8, device=dev)
-        s_x = torch.empty(1, dtype=torch.float32, device=dev)
-        ws = torch.empty(fq.fq_act_workspace_bytes(sp.K, Kpad), dtype=torch.uint8, device=dev)
-        f_act = lambda: fq.fq_flatten_quant_act(d["X"], lay.src, lay.rep, sp.bits, Xq, s_x, ws, absmax_in=d["a_static"])
-        gemm = fq.fq_gemm_i8 if sp.bits == 8 else fq.fq_gemm_i4
-        f_gemm = lambda: gemm(Xq, lay.Wq, s_x, lay.s_w, d["Y"])
+        f_act, f_gemm, xq_bytes, keep = kernels_of(d, lay)
         f_lin = lambda: lay.forward(d["X"], Y=d["Y"], absmax_in=d["a_static"])
         f_bf = lambda: fq.fq_gemm_bf16(d["Xb"], d["Wb"], d["Ybf"])
         t_act = event_time_ms(torch, f_act, args.steps)
@@ -172,14 +216,15 @@ def main():
         t_vendor_total += t_vendor
         flops = 2.0 * sp.M * Kpad * sp.N
         # algorithmic HBM bytes of flatten-quantize: X read once (static) or twice (dynamic), Xq written
-        act_bytes = sp.M * sp.K * d["X"].element_size() * (1 if args.static else 2) + sp.M * cols
+        act_bytes = sp.M * sp.K * d["X"].element_size() * (1 if args.static else 2) + xq_bytes
         if sp.bits == dom_bits:
             dom["flops"] += flops
             dom["ms"] += t_gemm
             dom["launches"] += 1
         fqa["bytes"] += act_bytes
         fqa["ms"] += t_act
-        row = dict(layer=d["name"], bits=sp.bits, M=sp.M, K=sp.K, N=sp.N, Kpad=Kpad,
+        row = dict(layer=d["name"], bits=sp.bits, storage={8: "int8", 4: "nibble", E3: "e3m2"}[lay.bits],
+                   M=sp.M, K=sp.K, N=sp.N, Kpad=Kpad,
                    ms_flatten_quant=round(t_act, 4), ms_gemm=round(t_gemm, 4), ms_linear=round(t_lin, 4),
                    ms_gemm_bf16=round(t_bf, 4), ms_vendor_bf16=round(t_vendor, 4),
                    gemm_tops=round(flops / t_gemm / 1e9, 1),
@@ -188,6 +233,20 @@ def main():
                    flatten_quant_gbs=round(act_bytes / t_act / 1e6, 1),
                    linear_eff_tops=round(2.0 * sp.M * sp.K * sp.N / t_lin / 1e9, 1),
                    speedup_vs_bf16=round(t_bf / t_lin, 3))
+        if d["lay_alt"] is not None:
+            la = d["lay_alt"]
+            fa_act, fa_gemm, _, keep_alt = kernels_of(d, la)
+            ta_act = event_time_ms(torch, fa_act, args.steps)
+            ta_gemm = event_time_ms(torch, fa_gemm, args.steps)
+            ta_lin = event_time_ms(torch, lambda: la.forward(d["X"], Y=d["Y"], absmax_in=d["a_static"]), args.steps)
+            fl_a = 2.0 * sp.M * la.Kpad * sp.N
+            alt["flops"] += fl_a
+            alt["ms"] += ta_gemm
+            alt["launches"] += 1
+            row["other_storage"] = dict(storage={4: "nibble", E3: "e3m2"}[la.bits], Kpad=la.Kpad,
+                                        ms_flatten_quant=round(ta_act, 4), ms_gemm=round(ta_gemm, 4),
+                                        ms_linear=round(ta_lin, 4), gemm_tops=round(fl_a / ta_gemm / 1e9, 1))
+            del keep_alt
         rows.append(row)
         log("[kernel] " + json.dumps(row))
         if args.sweep:
@@ -198,13 +257,30 @@ def main():
                 log(f"[sweep] {d['name']} variant {v}: int{sp.bits} gemm {tg:.4f} ms = {flops / tg / 1e9:.0f} TOPS; "
                     f"bf16 {tb:.4f} ms = {2.0 * sp.M * sp.K * sp.N / tb / 1e9:.0f} TFLOPS")
             fq.fq_gemm_select(args.variant)
-        del Xq, ws
+        del keep
     dom_avg_ms = dom["ms"] / dom["launches"]
     dom_achieved = dom["flops"] / dom["launches"] / dom_avg_ms / 1e9          # TOPS
-    roofline = dict(bound="mfma", kernel=f"gemm_dma_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
-                    peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4),
-                    traffic=MEASURED_TRAFFIC_BYTES.get((args.configs, args.variant, args.align)),
-                    avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.configs, args.variant, args.align, path))
+    if dom_bits == 4 and not args.nibble:
+        # E3M2 codes on the 6-bit MFMA: every multiply-add is an fp6 operation, priced against the fp6 peak
+        roofline = dict(bound="mfma", kernel="gemm_f6_wide_kernel (4-bit values as E3M2 codes, 6-bit MFMA)",
+                        achieved=round(dom_achieved, 1), peak=FP6_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(dom_achieved / FP6_PEAK_TFLOPS, 4), traffic=traffic,
+                        avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"],
+                        frac_of_int8_peak=round(dom_achieved / INT8_PEAK_TOPS, 4))
+    else:
+        roofline = dict(bound="mfma", kernel=f"gemm_dma_kernel<INT{dom_bits}> (int8 MFMA)", achieved=round(dom_achieved, 1),
+                        peak=INT8_PEAK_TOPS, unit="TOP/s", frac=round(dom_achieved / INT8_PEAK_TOPS, 4),
+                        traffic=traffic, avg_launch_ms=round(dom_avg_ms, 4), launches_per_step=dom["launches"])
+    other_path = None
+    if t_alt_ms is not None and alt["launches"]:
+        ops_alt = sum(2.0 * d["spec"].M * (d["lay_alt"] or d["lay"]).Kpad * d["spec"].N for d in layers)
+        a_tops = alt["flops"] / alt["ms"] / 1e9
+        a_peak = INT8_PEAK_TOPS if not args.nibble else FP6_PEAK_TFLOPS
+        other_path = dict(storage="nibble (int8 MFMA)" if not args.nibble else "e3m2 (6-bit MFMA)",
+                          ms_per_step=round(t_alt_ms, 4), value=round(ops_alt / (t_alt_ms * 1e-3) / 1e12, 2),
+                          gemm_achieved=round(a_tops, 1), gemm_peak=a_peak, gemm_frac=round(a_tops / a_peak, 4),
+                          timed_path_speedup=round(t_alt_ms / t_step_ms, 3))
     flatten_roofline = dict(bound="hbm", kernel="colabsmax + scale + flatten_quant", achieved=round(fqa["bytes"] / fqa["ms"] / 1e6, 1),
                             peak=HBM_PEAK_GBS, unit="GB/s", frac=round(fqa["bytes"] / fqa["ms"] / 1e6 / HBM_PEAK_GBS, 4))
 
@@ -293,7 +369,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int4+int8 (int8 MFMA, int32 accumulate; bf16 in/out)",
+        "dtype": ("int4+int8 (int8 MFMA, int32 accumulate; bf16 in/out)" if args.nibble else
+                  "int4 as e3m2 codes (6-bit MFMA, exact integer products, fp32 accumulate below 2^24) + int8 "
+                  "(int8 MFMA, int32 accumulate); bf16 in/out"),
         "data": "synthetic",
         "config": {"workload": "+".join(args.configs.split(",")) +
                                ": LLaMA-7B FFN pair 4096->11008->4096 INT4 and 4096->4096 INT8 projection, M=8192 tokens, "
@@ -301,7 +379,8 @@ def main():
                    "activation_scale": "static a'=T" if args.static else "dynamic per-tensor absmax",
                    "layers": [r["layer"] for r in rows], "gemm_variant": args.variant,
                    "launch": "one HIP graph per step, replayed" if args.graph else "eager",
-                   "kpad_align": args.align if args.align else "128 (INT8) / 256 (INT4)"},
+                   "int4_storage": "packed nibbles" if args.nibble else "E3M2 codes, k-blocked",
+                   "kpad_align": args.align if args.align else ("128 (INT8) / 256 (INT4)" if args.nibble else "128")},
         "pct_int8_mfma_peak": round(100.0 * value / INT8_PEAK_TOPS, 2),
         "effective_tops": round(ops_eff / (t_step_ms * 1e-3) / 1e12, 2),
         "speedup_vs_bf16": round(t_bf16_total / t_step_ms, 3),
@@ -310,6 +389,7 @@ def main():
         "ms_vendor_bf16_gemm_same_shapes": round(t_vendor_total, 4),
         "roofline": roofline,
         "flatten_quant_roofline": flatten_roofline,
+        "other_int4_storage": other_path,
         "cpu_baseline": cpu,
         "layers": rows,
         "bmm": bmm_rows,

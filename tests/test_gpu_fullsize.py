@@ -19,32 +19,40 @@ from tests.gpu_util import DEV, bf16_to_f64, rel_err, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _check_layer(cfg_name, idx, n_sample_rows=256, n_sample_cols=256, freivalds=2):
+E3 = fq.binding.FQ_BITS_I4_E3M2
+
+
+def _check_layer(cfg_name, idx, n_sample_rows=256, n_sample_cols=256, freivalds=2, e3m2=False):
+    """e3m2: the 4-bit layer in E3M2 storage on the 6-bit matrix pipe (what bench.py times for 4-bit layers):
+    same quantized integers as the nibble path, other bytes, other GEMM kernel."""
     cfg = WL.CONFIGS[cfg_name]
     print(f"[fullsize] generating {cfg_name} layer {idx}", flush=True)
     L = WL.make_layer(cfg, idx)
     sp = L.spec
     bits = sp.bits
     print(f"[fullsize] {cfg_name}.{sp.name} M={sp.M} K={sp.K} N={sp.N} bits={bits}", flush=True)
+    assert not e3m2 or bits == 4
     Wd = to_dev(L.W_store, sp.w_dtype)
-    lay = fq.FqLinear(Wd, L.chmax, L.T, bits)
+    lay = fq.FqLinear(Wd, L.chmax, L.T, E3 if e3m2 else bits)
     Xd = to_dev(L.X_store, sp.x_dtype)
+    stored = (lambda q: O.pack_e3m2_blocked(q).reshape(-1)) if e3m2 else \
+             (lambda q: (q.view(np.uint8) if bits == 8 else O.pack_i4(q)).reshape(-1))
     # --- map, weights ---
-    src, rep, kp, kpad = O.plan(L.chmax, L.T, 128 if bits == 8 else 256)
+    src, rep, kp, kpad = O.plan(L.chmax, L.T, 128 if (bits == 8 or e3m2) else 256)
     assert (lay.src_host == src).all() and (lay.rep_host == rep).all() and lay.Kpad == kpad
     Wq_o, s_w_o = O.flatten_weights(L.W, src, bits)
-    Wq_g = lay.Wq.cpu().numpy().view(np.uint8)
+    Wq_g = lay.Wq.cpu().numpy().view(np.uint8).reshape(-1)
     assert np.float32(lay.s_w.item()) == s_w_o
-    assert np.array_equal(Wq_g, Wq_o.view(np.uint8) if bits == 8 else O.pack_i4(Wq_o))
+    assert np.array_equal(Wq_g, stored(Wq_o))
     print("[fullsize]   map, weights and s_w equal the oracle's", flush=True)
     # --- quantized activations (the workspace of fq_linear starts with X'q) ---
     acc_g = lay.forward(Xd, out_dtype=torch.int32)
     torch.cuda.synchronize()
-    cols = kpad if bits == 8 else kpad // 2
-    Xq_g = lay.workspace(sp.M)[: sp.M * cols].view(sp.M, cols).cpu().numpy()
+    cols = kpad // 4 * 3 if e3m2 else (kpad if bits == 8 else kpad // 2)
+    Xq_g = lay.workspace(sp.M)[: sp.M * cols].cpu().numpy()
     a = O.act_absmax_dynamic(L.X, src, rep)
     Xq_o, s_x_o = O.flatten_quant_act(L.X, src, rep, bits, a)
-    assert np.array_equal(Xq_g, Xq_o.view(np.uint8) if bits == 8 else O.pack_i4(Xq_o))
+    assert np.array_equal(Xq_g, stored(Xq_o))
     acc_g = acc_g.cpu().numpy()
     print("[fullsize]   quantized activations equal the oracle's", flush=True)
     # --- sampled rows, recomputed by the oracle ---
@@ -88,6 +96,12 @@ def test_cfg2_full():
 @pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg3i8", 0)])
 def test_benchmark_layers_full_size(cfg, idx):
     _check_layer(cfg, idx)
+
+
+@pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg4", 2), ("cfg5", 3), ("cfgP", 1)])
+def test_four_bit_layers_in_e3m2_storage_full_size(cfg, idx):
+    """The 4-bit layers as the benchmark runs them: E3M2 storage, 6-bit matrix pipe."""
+    _check_layer(cfg, idx, freivalds=1, e3m2=True)
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
