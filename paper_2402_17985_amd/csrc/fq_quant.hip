@@ -30,26 +30,23 @@ typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 // 12 bytes at 4-byte alignment (a 3-element vector type would claim 16)
 struct __attribute__((aligned(4))) u3 { uint32_t a, b, c; };
 
-// 6-bit E3M2 code (sign, 3 exponent bits with bias 3, 2 mantissa bits) of an integer q in [-8, 8]: the
-// fp32 form of |q| already holds the exponent and, in its top mantissa bits, the two mantissa bits.
-__device__ __forceinline__ uint32_t e3m2_code(int q)
+// 6-bit E3M2 code (sign, 3 exponent bits with bias 3, 2 mantissa bits) of an integer-valued float r in
+// [-8, 8]: the fp32 form of |r| already holds the exponent and, in its top mantissa bits, the two
+// mantissa bits (exponent field 127 + e -> 3 + e: subtract 124 << 2 after the shift); 0 -> 0.
+__device__ __forceinline__ int e3m2_code_of_float(float r)
 {
-    const int a = q < 0 ? -q : q;
-    const uint32_t mag = a ? (__float_as_uint((float)a) >> 21) - ((127u - 3u) << 2) : 0u;
-    return (q < 0 ? 0x20u : 0u) | mag;
+    const uint32_t bits = __float_as_uint(r + 0.0f);                   // -0 -> +0
+    const int mag = max((int)((bits & 0x7fffffffu) >> 21) - (124 << 2), 0);
+    return mag | (int)((bits >> 26) & 0x20u);
 }
-// 16 codes as a 96-bit little-endian bit stream
-__device__ __forceinline__ u3 pack16_e3m2(const int (&q)[16])
+// 16 codes as a 96-bit little-endian bit stream (code i in bits 6 i .. 6 i + 5)
+__device__ __forceinline__ u3 pack16_e3m2(const int (&c)[16])
 {
-    unsigned long long lo = 0, hi = 0;       // lo: slots 0..9 (60 bits) + 4 bits of slot 10; hi: the rest
+    uint32_t g[4];                                                     // four codes = 24 bits
 #pragma unroll
-    for (int i = 0; i < 10; ++i) lo |= (unsigned long long)e3m2_code(q[i]) << (6 * i);
-    const unsigned long long c10 = e3m2_code(q[10]);
-    lo |= c10 << 60;
-    hi = c10 >> 4;
-#pragma unroll
-    for (int i = 11; i < 16; ++i) hi |= (unsigned long long)e3m2_code(q[i]) << (6 * i - 64);
-    return u3{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi};
+    for (int i = 0; i < 4; ++i)
+        g[i] = (uint32_t)c[4 * i] | ((uint32_t)c[4 * i + 1] << 6) | ((uint32_t)c[4 * i + 2] << 12) | ((uint32_t)c[4 * i + 3] << 18);
+    return u3{g[0] | (g[1] << 24), (g[1] >> 8) | (g[2] << 16), (g[2] >> 16) | (g[3] << 8)};
 }
 
 template <int DT> struct Elem;
@@ -352,7 +349,8 @@ __global__ __launch_bounds__(1024) void scale_kernel(const uint32_t* __restrict_
 // ---------------------------------------------------------------------------------------------
 // flatten + quantize
 // ---------------------------------------------------------------------------------------------
-// BITS = 8, 4, or 6 = the 4-bit quantizer with its values stored as 6-bit E3M2 codes (k-blocked layout)
+// BITS = 8, 4, or 6 = the 4-bit quantizer with its values stored as 6-bit E3M2 codes (k-blocked layout);
+// for 6 the result is the code itself, which is also what the row strip keeps in LDS
 template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
 {
     constexpr int QB = (BITS == 6) ? 4 : BITS;
@@ -360,7 +358,8 @@ template <int BITS> __device__ __forceinline__ int quant1(float x, float m)
     constexpr float lo = -(float)(1 << (QB - 1));
     float r = rintf(x * m);                 // one fp32 multiply, then round-half-even
     r = fminf(fmaxf(r, lo), hi);
-    return (int)r;
+    if constexpr (BITS == 6) return e3m2_code_of_float(r);
+    else return (int)r;
 }
 
 // PEEL = false: slot value x * m_p (equal split; m_p from mslot).  PEEL = true: the printed split of
