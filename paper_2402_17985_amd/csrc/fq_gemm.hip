@@ -962,7 +962,7 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
     constexpr int WAIT_TWO = ((2 * LPS) & 0xf) | (((2 * LPS) >> 4) << 14) | 0x0f70;
     constexpr int WAIT_ALL = 0x0f70;
     static_assert((BM * CPR) % (64 * NW) == 0 && (BN * CPR) % (64 * NW) == 0, "copy blocks must tile the stage");
-    static_assert(2 * LPS < 64 && NR <= NM, "pipeline shape");
+    static_assert(2 * LPS < 64 && 2 * NR <= 2 * NM && LPS <= 2 * NM, "pipeline shape");
     typedef v16f acc_t;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1049,20 +1049,24 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
     auto slice = [&](int cur, const uint8_t* rs, int rks, auto rd_tag, auto copy_tag, int copy_stage) {
         constexpr bool rd = decltype(rd_tag)::value;
         constexpr bool cp = decltype(copy_tag)::value;
-        static_assert(LPS <= NM, "one copy per MFMA slot");
 #pragma unroll
         for (int t = 0; t < NM; ++t) {
             const int i = t / FN, j = t % FN;
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(opb[cur][j], opa[cur][i], acc[i][j], 3, 3, 0, 127, 0, 127);
+            // The 2 NR LDS reads of the next slice's operands (16-byte, then 8-byte piece of operand 0, 1, ...)
+            // and the LPS copy instructions are spread evenly over the NM MFMA slots.  An operand is needed
+            // by the next slice's MFMA 0 (operands 0, 1), MFMA j (operand 1 + j) or MFMA FN i (operand FN + i):
+            // always a full slice after its read.
             if constexpr (rd) {
-                // one LDS read per MFMA: operand t/2 of the next slice (its first MFMA needs operands 0
-                // and 1, MFMA j operand 1 + j, MFMA 4 i operand 4 + i: all read at least one slice earlier)
-                static_assert(NM == 2 * NR, "one LDS read per MFMA slot");
-                if (t & 1) read_y(rs, rks, cur ^ 1, t >> 1);
-                else read_x(rs, rks, cur ^ 1, t >> 1);
+#pragma unroll
+                for (int q = t * (2 * NR) / NM; q < (t + 1) * (2 * NR) / NM; ++q) {
+                    if (q & 1) read_y(rs, rks, cur ^ 1, q >> 1);
+                    else read_x(rs, rks, cur ^ 1, q >> 1);
+                }
             }
             if constexpr (cp) {
-                if (t >= NM - LPS) issue_one(copy_stage, t - (NM - LPS));
+#pragma unroll
+                for (int q = t * LPS / NM; q < (t + 1) * LPS / NM; ++q) issue_one(copy_stage, q);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1109,18 +1113,30 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
                                    smem + wave * (64 * TN * 2), bias);
 }
 
+// Workgroups [0, n_main) compute 256 x 256 tiles; a last, partly filled round of at most half the CUs is
+// computed as 128 x 256 halves by workgroups [n_main, n_main + 2 n_tail), so that it takes about half as long.
 __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B,
                                                            int M, int N, int rowbytes, const float* __restrict__ s_x,
                                                            const float* __restrict__ s_w, void* __restrict__ Y,
-                                                           int y_dtype, int ldy, int tiles_m, int tiles_n, Batch bt)
+                                                           int y_dtype, int ldy, int tiles_m, int tiles_n, int n_main,
+                                                           Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
     Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
     int tile_m, tile_n;
-    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
-    gemm_f6_wide_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt.bias);
+    const int v = blockIdx.x;
+    if (v < n_main) {
+        tile_of_workgroup(v, n_main, tiles_m, tiles_n, tile_m, tile_n);
+        gemm_f6_wide_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+                                    bt.bias);
+    } else {
+        const int t = v - n_main;
+        tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
+        gemm_f6_wide_tile<128, 256>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y,
+                                    y_dtype, ldy, bt.bias);
+    }
 }
 
 __global__ __launch_bounds__(512) void gemm_f6_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, int M,
@@ -1379,10 +1395,19 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
     if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
     static bool attr_set_wide = false;
     if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel), smem, attr_set_wide)) return rc;
-    if (forced_gemm_variant() != 0)
-        gemm_f6_wide_kernel<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(256), smem, stream>>>(
+    if (forced_gemm_variant() != 0) {
+        // a last round that would occupy at most half of the CUs is run as half-height tiles instead
+        const int cus = compute_units();
+        const int r = (int)(tiles % cus);
+        int n_main = (int)tiles, n_tail = 0;
+        if (bt.count == 1 && r > 0 && 2 * r <= cus) {
+            n_tail = r;
+            n_main = (int)tiles - r;
+        }
+        gemm_f6_wide_kernel<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
             static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
-            tiles_m, tiles_n, bt);
+            tiles_m, tiles_n, n_main, bt);
+    }
     else
         gemm_f6_kernel<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(512), smem, stream>>>(
             static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
