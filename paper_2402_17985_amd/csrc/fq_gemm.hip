@@ -765,6 +765,188 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
 }
 
 // =============================================================================================
+// gemm_wide_kernel (INT8, bf16): four waves with 128 x 128 wave tiles
+// =============================================================================================
+// The ping-pong kernel's 128 x 64 wave tiles fetch 3/4 of an operand from LDS per MFMA; at the INT8 and
+// bf16 rates that read stream plus the copies' writes keeps the LDS as busy as the matrix pipe.  Here a
+// wave owns 128 x 128 of the output (256 accumulator registers per lane, in AGPRs; one wave per SIMD),
+// which needs 1/2 operand per MFMA.  A single wave has to issue everything itself, so the work is dealt
+// out by MFMA slot: one 16-byte LDS read of the next k-slice's operands after every second MFMA
+// (operands double-buffered in registers) and, during a stage's last k-slice, one global->LDS copy
+// instruction per MFMA for the stage after next.  Two stage buffers of 128 bytes per row; the barrier
+// sits before the last k-slice of a stage, when every wave holds that slice in registers: it frees the
+// stage's buffer for those copies and publishes the next stage (each wave has waited for its own
+// copies), and the last slice's MFMAs overlap the first reads of the next stage.
+// Measured 12-20 % slower than the ping-pong kernel (INT8 2.1 against 2.4 POP/s, 2.6 against 3.2 on zero
+// operands): two 64 KiB buffers are all that fits, so a stage's copies start only three k-slices before
+// they are waited for.  The 6-bit kernel of the same shape (48 KiB stages, ring of three) does not have
+// that limit.  Selectable as variant 11.
+template <int MODE, int BM, int BN>
+__device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
+                                               const uint8_t* __restrict__ B, int M, int N, int rowbytes,
+                                               const float* __restrict__ s_x, const float* __restrict__ s_w,
+                                               void* __restrict__ Y, int y_dtype, int ldy,
+                                               const float* __restrict__ bias)
+{
+    static_assert(MODE == MODE_I8 || MODE == MODE_BF16, "16-byte operands per lane");
+    constexpr int WM = 2, WN = 2, NW = 4, NSTAGE = 2, BKB = 128;
+    constexpr int CPR = BKB / 16, RPB = 64 / CPR;
+    constexpr int A_BLOCKS = BM / RPB / NW, B_BLOCKS = BN / RPB / NW, LPS = A_BLOCKS + B_BLOCKS;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int KS = BKB / 32;                     // k-slices per stage
+    constexpr int NR = FM + FN, NM = FM * FN;
+    constexpr int STAGE = (BM + BN) * BKB;
+    constexpr int SWZ_SHIFT = 1, SWZ_MASK = 7;
+    static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "copy blocks must tile the stage");
+    typedef typename Acc<MODE>::type acc_t;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk_full = rowbytes / BKB;
+    const int nk = nk_full + ((rowbytes % BKB) ? 1 : 0);
+
+    // copy mapping as in gemm_dma_tile: block b covers rows b RPB .. +RPB-1, lane i lands at
+    // (row b RPB + i / CPR, stored chunk i % CPR) and fetches global chunk (i % CPR) ^ swz(row)
+    const int drow = lane / CPR;
+    const int dsw = ((wave * RPB + drow) >> SWZ_SHIFT) & SWZ_MASK;
+    const int dchunk = (lane % CPR) ^ dsw;
+    static_assert((RPB * NW) % 16 == 0, "swizzle must repeat across a wave's copy blocks");
+    uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
+#pragma unroll
+    for (int j = 0; j < A_BLOCKS; ++j)
+        offA[j] = (uint32_t)min(m0 + (wave + j * NW) * RPB + drow, M - 1) * (uint32_t)rowbytes + dchunk * 16;
+#pragma unroll
+    for (int j = 0; j < B_BLOCKS; ++j)
+        offB[j] = (uint32_t)min(n0 + (wave + j * NW) * RPB + drow, N - 1) * (uint32_t)rowbytes + dchunk * 16;
+    const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
+    const uint8_t* zero16 = reinterpret_cast<const uint8_t*>(g_zero_chunk);
+    // copy instruction idx (0 .. LPS-1) of a stage: the A blocks, then the B blocks; in the last, partial
+    // stage lanes whose chunk lies at or beyond the row end fetch 16 zero bytes instead
+    auto issue_one = [&](int stage_index, int idx) {
+        const uint32_t sA = lds0 + (stage_index % NSTAGE) * STAGE;
+        const int kb = stage_index * BKB;
+        const bool isA = idx < A_BLOCKS;
+        const int j = isA ? idx : idx - A_BLOCKS;
+        const uint8_t* g = (isA ? A : B) + kb;
+        const uint32_t off = isA ? offA[j] : offB[j];
+        const uint32_t dst = (isA ? sA : sA + BM * BKB) + j * NW * 1024;
+        if (stage_index < nk_full) dma16(g, off, dst);
+        else dma16_addr((kb + dchunk * 16 < rowbytes) ? g + off : zero16, dst);
+    };
+    auto issue_all = [&](int stage_index) {
+#pragma unroll
+        for (int q = 0; q < LPS; ++q) issue_one(stage_index, q);
+    };
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = (frow >> SWZ_SHIFT) & SWZ_MASK;
+    int kofs[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kofs[ks] = ((2 * ks + fhalf) ^ fsw) << 4;
+    const int a_rd = (wm * TM + frow) * BKB, b_rd = BM * BKB + (wn * TN + frow) * BKB;
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // operands in the order the MFMA walk (i outer, j inner) first needs them: a0, b0 .. b(FN-1), a1 ..
+    v4i opa[2][FM], opb[2][FN];
+    auto read_op = [&](const uint8_t* st, int ks, int buf, int r) {
+        if (r == 0) opa[buf][0] = *reinterpret_cast<const v4i*>(st + a_rd + kofs[ks]);
+        else if (r <= FN) opb[buf][r - 1] = *reinterpret_cast<const v4i*>(st + b_rd + (r - 1) * 32 * BKB + kofs[ks]);
+        else opa[buf][r - FN] = *reinterpret_cast<const v4i*>(st + a_rd + (r - FN) * 32 * BKB + kofs[ks]);
+    };
+    // the MFMAs of the slice in buffer `cur`; the NR reads of slice `rks` of stage `rs` (into the other
+    // buffer) and, when cp, the LPS copies of `copy_stage` are spread evenly over the NM slots
+    auto slice = [&](int cur, const uint8_t* rs, int rks, auto rd_tag, auto copy_tag, int copy_stage) {
+        constexpr bool rd = decltype(rd_tag)::value;
+        constexpr bool cp = decltype(copy_tag)::value;
+#pragma unroll
+        for (int t = 0; t < NM; ++t) {
+            const int i = t / FN, j = t % FN;
+            if constexpr (MODE == MODE_I8)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opb[cur][j], opa[cur][i], acc[i][j], 0, 0, 0);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, opb[cur][j]),
+                                                                   __builtin_bit_cast(v8bf, opa[cur][i]), acc[i][j], 0, 0, 0);
+            if constexpr (rd) {
+#pragma unroll
+                for (int q = t * NR / NM; q < (t + 1) * NR / NM; ++q) read_op(rs, rks, cur ^ 1, q);
+            }
+            if constexpr (cp) {
+#pragma unroll
+                for (int q = t * LPS / NM; q < (t + 1) * LPS / NM; ++q) issue_one(copy_stage, q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    typedef std::true_type yes;
+    typedef std::false_type no;
+
+    issue_all(0);
+    __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
+    __syncthreads();
+    if (nk > 1) issue_all(1);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) read_op(smem, 0, 0, r);
+    __builtin_amdgcn_sched_barrier(0);
+
+    static_assert(KS % 2 == 0, "operand buffers alternate per slice");
+    // one stage: slices 0 .. KS-2 (each reads the next slice of the stage), the barrier, the last slice
+    // (reads slice 0 of the next stage; when copy_tag, copies stage kt+2 into the buffer just freed)
+    auto stage = [&](int kt, auto next_tag, auto copy_tag) {
+        const uint8_t* s = smem + (kt & 1) * STAGE;
+        const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < KS - 1; ++ks) slice(ks & 1, s, ks + 1, yes{}, no{}, 0);
+        // the last slice's operands are in registers; my copies of stage kt+1 (issued a stage ago) landed
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        slice((KS - 1) & 1, sn, 0, next_tag, copy_tag, kt + 2);
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) stage(kt, yes{}, yes{});
+    for (; kt + 1 < nk; ++kt) stage(kt, yes{}, no{});
+    stage(kt, no{}, no{});
+    __syncthreads();                                 // every wave is past its last LDS operand read
+
+    store_tile<MODE, FM, FN, 2>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+                                smem + wave * (64 * TN * 2), bias);
+}
+
+// Workgroups [0, n_main) compute 256 x 256 tiles; a last, partly filled round of at most half the CUs is
+// computed as 128 x 256 halves by workgroups [n_main, n_main + 2 n_tail).
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, int M,
+                                                        int N, int rowbytes, const float* __restrict__ s_x,
+                                                        const float* __restrict__ s_w, void* __restrict__ Y, int y_dtype,
+                                                        int ldy, int tiles_m, int tiles_n, int n_main, Batch bt)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    A += (size_t)blockIdx.y * bt.stride_a;
+    B += (size_t)blockIdx.y * bt.stride_b;
+    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
+    int tile_m, tile_n;
+    const int v = blockIdx.x;
+    if (v < n_main) {
+        tile_of_workgroup(v, n_main, tiles_m, tiles_n, tile_m, tile_n);
+        gemm_wide_tile<MODE, 256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+                                       bt.bias);
+    } else {
+        const int t = v - n_main;
+        tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
+        gemm_wide_tile<MODE, 128, 256>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w,
+                                       Y, y_dtype, ldy, bt.bias);
+    }
+}
+
+#if FQ_GEMM_MODE == 3
+// =============================================================================================
 // gemm_f6_kernel: 4-bit operands stored as 6-bit E3M2 codes, multiplied on the 6-bit matrix pipe
 // =============================================================================================
 // v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in the E3M2 format runs at twice the INT8 rate.
@@ -1153,6 +1335,8 @@ __global__ __launch_bounds__(512) void gemm_f6_kernel(const uint8_t* __restrict_
     gemm_f6_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt.bias);
 }
 
+#endif  // FQ_GEMM_MODE == 3
+
 // =============================================================================================
 // gemm_reg_kernel: global -> registers -> LDS
 // =============================================================================================
@@ -1343,6 +1527,39 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
 }
 
 template <int MODE>
+int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w, void* Y,
+                int y_dtype, int ldy, Batch bt, hipStream_t stream)
+{
+    if constexpr (MODE == MODE_I8 || MODE == MODE_BF16) {
+        if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
+            return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
+        auto kern = gemm_wide_kernel<MODE>;
+        constexpr int smem = 2 * 512 * 128;
+        static bool attr_set = false;
+        if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
+        const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+        const long long tiles = (long long)tiles_m * tiles_n;
+        if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
+        // a last round that would occupy at most half of the CUs is run as half-height tiles instead
+        const int cus = compute_units();
+        const int r = (int)(tiles % cus);
+        int n_main = (int)tiles, n_tail = 0;
+        if (bt.count == 1 && r > 0 && 2 * r <= cus) {
+            n_tail = r;
+            n_main = (int)tiles - r;
+        }
+        kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
+            static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+            tiles_m, tiles_n, n_main, bt);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
+        return FQ_OK;
+    } else {
+        return fail(FQ_ERR_RANGE, "GEMM variant 11 exists for INT8 and bf16 operands only");
+    }
+}
+
+template <int MODE>
 int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
              void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
@@ -1368,6 +1585,7 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 10: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 11: return launch_wide<MODE>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
 }

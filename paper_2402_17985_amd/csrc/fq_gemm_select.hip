@@ -5,7 +5,7 @@
 namespace fq {
 
 namespace {
-constexpr int NUM_VARIANTS = 11;
+constexpr int NUM_VARIANTS = 12;
 // Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
 int g_variant = -1;
 }  // namespace

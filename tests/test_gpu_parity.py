@@ -245,7 +245,7 @@ def test_linear_is_deterministic():
 # ------------------------------------------------------------------------------------------
 # bf16 baseline GEMM
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [0, 2])
+@pytest.mark.parametrize("variant", [0, 2, 11])
 def test_gemm_bf16_baseline(variant):
     rng = np.random.default_rng(9)
     M, N, K = 300, 260, 1032
@@ -591,3 +591,57 @@ def test_gemm_more_tiles_than_compute_units(bits):
     y_ref = O.dequant(ref, np.float32(0.01), np.float32(0.003))
     assert rel_err(bf16_to_f64(Y[:, :N]), y_ref).max() <= 2.0 ** -8
     assert not Y[:, N:].any()
+
+
+# ------------------------------------------------------------------------------------------
+# the four-wave kernel with 128 x 128 wave tiles (INT8 and bf16 only)
+# ------------------------------------------------------------------------------------------
+def test_gemm_four_wave_kernel_int8():
+    """Variant 11: raw accumulators on ragged shapes (masked last k-stage, one-stage and two-stage reductions),
+    a grid with half-height tail tiles, the staged 2-byte epilogue with bias, and a batched launch."""
+    rng = np.random.default_rng(1100)
+    fq.fq_gemm_select(11)
+    try:
+        for (M, N, Kpad) in [(300, 520, 416), (257, 129, 1056), (1, 1, 32), (33, 700, 160), (512, 256, 128), (70, 41, 256),
+                             (17 * 256 - 20, 16 * 256 - 7, 160)]:
+            Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
+            assert np.array_equal(_gemm_acc(Xq, Wq, 8), O.gemm_i32(Xq, Wq)), (M, N, Kpad)
+        lo = -128
+        Xq = np.full((40, 26016), lo, np.int8)
+        Wq = np.full((70, 26016), lo, np.int8)
+        Wq[1::2] = 127
+        assert np.array_equal(_gemm_acc(Xq, Wq, 8), O.gemm_i32(Xq, Wq))
+        # epilogue: bf16 with bias, padded row stride
+        M, N, Kpad = 300, 333, 512
+        Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
+        s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+        bias = rng.normal(0, 3.0, N).astype(np.float32)
+        Ybuf = torch.full((M, 384), 7.0, dtype=torch.bfloat16, device=DEV)
+        fq.fq_gemm_i8_bias(torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV), scalar(s_x), scalar(s_w),
+                           torch.from_numpy(bias).to(DEV), Ybuf[:, :N])
+        torch.cuda.synchronize()
+        acc = O.gemm_i32(Xq, Wq)
+        prod = O.dequant(acc, s_x, s_w)
+        denom = np.abs(prod) + np.abs(bias.astype(np.float64))[None, :] + 1e-300
+        got = Ybuf[:, :N].float().cpu().numpy().astype(np.float64)
+        assert (np.abs(got - O.dequant_bias(acc, s_x, s_w, bias)) / denom).max() <= 2.0 ** -8
+        assert (Ybuf[:, N:].float() == 7.0).all()
+        # batched
+        Aq, Bq = _bmm_operands(7, 3, 260, 300, 192, 8)
+        Y = torch.full((3, 260, 300), -1, dtype=torch.int32, device=DEV)
+        fq.fq_bmm_i8(_to_dev_q(Aq, 8), _to_dev_q(Bq, 8), None, None, Y)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy(), O.bmm_i32(Aq, Bq))
+    finally:
+        fq.fq_gemm_select(-1)
+
+
+def test_gemm_four_wave_kernel_rejects_nibbles():
+    fq.fq_gemm_select(11)
+    try:
+        Xq = torch.zeros((4, 16), dtype=torch.uint8, device=DEV)
+        Y = torch.zeros((4, 4), dtype=torch.int32, device=DEV)
+        with pytest.raises(fq.FqError, match="FQ_ERR_RANGE"):
+            fq.fq_gemm_i4(Xq, Xq, None, None, Y)
+    finally:
+        fq.fq_gemm_select(-1)
