@@ -208,3 +208,24 @@ def test_peel_split_has_no_e3m2_form():
                                      torch.zeros(1, dtype=torch.float32, device=DEV),
                                      bytes_ws(fq.fq_act_workspace_bytes(K, kpad)))
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("Kpad", [128, 256, 384, 1024])
+def test_gemm_e3m2_several_rounds_of_tiles(Kpad):
+    """600 tiles on a 256-CU device: two rounds of full tiles and a round of half-height tiles; reductions of
+    one, two, three (= the ring) and eight stages.  Sampled rows and columns against the oracle, bf16 epilogue."""
+    rng = np.random.default_rng(1300 + Kpad)
+    M, N = 25 * 256 - 20, 24 * 256 - 7
+    Xq, Wq = _rand_q4(rng, M, Kpad), _rand_q4(rng, N, Kpad)
+    got = _acc(Xq, Wq, 1)
+    rows = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1, 255, 256, 3071, 3072]]))
+    cols = np.unique(np.concatenate([rng.integers(0, N, 40), [0, N - 1, 255, 256]]))
+    assert np.array_equal(got[rows], O.gemm_i32(Xq[rows], Wq))
+    assert np.array_equal(got[:, cols], O.gemm_i32(Xq, Wq[cols]))
+    Y = torch.zeros((M, N + 7), dtype=torch.bfloat16, device=DEV)
+    fq.fq_gemm_i4_e3m2(torch.from_numpy(O.pack_e3m2_blocked(Xq)).to(DEV), torch.from_numpy(O.pack_e3m2_blocked(Wq)).to(DEV),
+                       scalar(0.01), scalar(0.003), None, Y[:, :N])
+    torch.cuda.synchronize()
+    y_ref = O.dequant(O.gemm_i32(Xq[rows], Wq), np.float32(0.01), np.float32(0.003))
+    assert rel_err(bf16_to_f64(Y[torch.from_numpy(rows).to(DEV)][:, :N]), y_ref).max() <= 2.0 ** -8
+    assert not Y[:, N:].any()

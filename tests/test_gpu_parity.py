@@ -536,10 +536,11 @@ def test_flatten_quant_act_irregular_map(bits, static):
 # ------------------------------------------------------------------------------------------
 # the calls are capturable: no allocation, no synchronization, clears done by fill kernels
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("bits", [8, 4, 6])
 def test_linear_replayed_from_a_graph(bits):
     """fq_linear captured once into a HIP graph and replayed with new inputs between replays: every
-    replay equals the eager call on the same input (raw accumulators, so the comparison is exact)."""
+    replay equals the eager call on the same input (raw accumulators, so the comparison is exact).
+    bits = 6: the 4-bit layer in E3M2 storage."""
     L = _layer("cfg3", M_override=300, K_override=1024, N_override=264)
     M, K = L.X.shape
     N = L.W.shape[0]
@@ -566,8 +567,9 @@ def test_linear_replayed_from_a_graph(bits):
         assert torch.equal(Yg, Ye), f"replay {rnd} differs from the eager call"
     # and the eager result is the oracle's on the last input
     Xh = X.float().cpu().numpy()
-    Wq_ref, s_w_ref = O.flatten_weights(L.W, lay.src_host, bits)
-    acc_ref, _, _ = O.linear(Xh, lay.src_host, lay.rep_host, Wq_ref, s_w_ref, bits, want_y=False)
+    qbits = 4 if bits == 6 else bits
+    Wq_ref, s_w_ref = O.flatten_weights(L.W, lay.src_host, qbits)
+    acc_ref, _, _ = O.linear(Xh, lay.src_host, lay.rep_host, Wq_ref, s_w_ref, qbits, want_y=False)
     np.testing.assert_array_equal(Ye.cpu().numpy(), acc_ref)
 
 
