@@ -95,7 +95,7 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int nwg, int tiles_m, 
 }
 __device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tile_m, int& tile_n)
 {
-    constexpr int GROUP_M = 8;
+    constexpr int GROUP_M = 8;     // 2, 4, 16, 32 measured 1-7 % slower on the 6-bit kernel
     const int group = GROUP_M * tiles_n;
     const int gidx = logical / group;
     const int first_m = gidx * GROUP_M;
