@@ -229,3 +229,34 @@ def test_gemm_e3m2_several_rounds_of_tiles(Kpad):
     y_ref = O.dequant(O.gemm_i32(Xq[rows], Wq), np.float32(0.01), np.float32(0.003))
     assert rel_err(bf16_to_f64(Y[torch.from_numpy(rows).to(DEV)][:, :N]), y_ref).max() <= 2.0 ** -8
     assert not Y[:, N:].any()
+
+
+def test_two_sided_flatten_e3m2():
+    """Weight-side flattening with both tensors in E3M2 storage: bytes, scales and accumulators bit-exact."""
+    L = _layer("cfg3", M_override=300, K_override=1024, N_override=200)
+    M, K = L.X.shape
+    N = L.W.shape[0]
+    rng = np.random.default_rng(9)
+    W = L.W.copy()
+    W[:, rng.choice(K, 12, replace=False)] *= np.float32(5.0)
+    W_store, W = WL.round_to_dtype(W, L.spec.w_dtype)
+    cw = np.abs(W).max(axis=0)
+    T_w = float(np.float32(2.0 * np.median(cw)))
+    src, rx, rw, od, kp, kpad = fq.fq_flatten_plan_xw(L.chmax, float(L.T), cw, T_w, align=128)
+    assert (rw > 1).any() and (rx > 1).any()
+    Wq_ref, s_w_ref = O.flatten_weights_split(W, src, rw, 4)
+    Xq_ref, s_x_ref = O.flatten_quant_act(L.X, src, rx, 4, O.act_absmax_dynamic(L.X, src, rx))
+    Wq = torch.full((kpad // 128, N, 96), 0x55, dtype=torch.uint8, device=DEV)
+    Xq = torch.full((kpad // 128, M, 96), 0x55, dtype=torch.uint8, device=DEV)
+    s_w, s_x = scalar(0.0), scalar(0.0)
+    ws = bytes_ws(fq.fq_act_workspace_bytes(K, kpad))
+    srcd = dev_i32(src)
+    fq.fq_flatten_weights_split(to_dev(W_store, L.spec.w_dtype), srcd, dev_i32(rw), E3, Wq, s_w, ws)
+    fq.fq_flatten_quant_act(to_dev(L.X_store, L.spec.x_dtype), srcd, dev_i32(rx), E3, Xq, s_x, ws)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    fq.fq_gemm_i4_e3m2(Xq, Wq, None, None, None, acc)
+    torch.cuda.synchronize()
+    assert np.float32(s_w.item()) == s_w_ref and np.float32(s_x.item()) == s_x_ref
+    np.testing.assert_array_equal(Wq.cpu().numpy(), O.pack_e3m2_blocked(Wq_ref))
+    np.testing.assert_array_equal(Xq.cpu().numpy(), O.pack_e3m2_blocked(Xq_ref))
+    np.testing.assert_array_equal(acc.cpu().numpy(), O.gemm_i32(Xq_ref, Wq_ref))
