@@ -122,6 +122,17 @@ template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typenam
 {
     if constexpr (MODE == MODE_BF16) {
         return (__bf16)acc[r];
+    } else if constexpr (MODE == MODE_F6) {
+        // the fp32 accumulator holds the integer result exactly (|acc| < 2^24): it is fl32(acc) already
+        if constexpr (YDT == FQ_I32) {
+            return (int)acc[r];
+        } else {
+            float f = acc[r] * scale;
+            if (has_bias) f += b;
+            if constexpr (YDT == FQ_F32) return f;
+            else if constexpr (YDT == FQ_BF16) return (__bf16)f;
+            else return (_Float16)f;
+        }
     } else {
         int v = acc[r];
         if (MODE == MODE_I4) v >>= 8;
