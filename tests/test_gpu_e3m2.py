@@ -260,3 +260,23 @@ def test_two_sided_flatten_e3m2():
     np.testing.assert_array_equal(Wq.cpu().numpy(), O.pack_e3m2_blocked(Wq_ref))
     np.testing.assert_array_equal(Xq.cpu().numpy(), O.pack_e3m2_blocked(Xq_ref))
     np.testing.assert_array_equal(acc.cpu().numpy(), O.gemm_i32(Xq_ref, Wq_ref))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_gemm_e3m2_units_on_top_of_the_largest_sums(variant):
+    """Exactness where it is tightest: accumulators close to the largest magnitude the interface admits (2^23),
+    built from products of 64, with products of +-1, +-3 and +-7 mixed in, so that the result depends on the
+    lowest bit of an fp32 accumulator that large.  Positions of the small products cover every k-slot of an
+    MFMA and both ends of the reduction."""
+    Kpad = 131072 - 128
+    rng = np.random.default_rng(23)
+    Xq = np.full((6, Kpad), -8, np.int8)
+    Wq = np.full((9, Kpad), -8, np.int8)
+    small = np.concatenate([np.arange(0, 64), rng.choice(np.arange(64, Kpad - 64), 501, replace=False),
+                            np.arange(Kpad - 64, Kpad)])
+    Xq[:, small] = rng.choice(np.array([1, -1], np.int8), (6, small.size))
+    Wq[:, small] = rng.choice(np.array([1, -1, 3, -3, 7, -7], np.int8), (9, small.size))
+    Wq[4] = -Wq[4]                                   # the same magnitudes on the negative side
+    ref = O.gemm_i32(Xq, Wq)
+    assert np.abs(ref).max() > (1 << 23) - (1 << 17) and (ref & 1).any()
+    assert np.array_equal(_acc(Xq, Wq, variant), ref)
