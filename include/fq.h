@@ -127,7 +127,9 @@ int fq_smooth_scales(const float* chmax_x_host, const float* chmax_w_host, int K
  *   All-zero W: Wq_out = 0, s_w = 1.
  *
  * W        [N, K] device, w_dtype in {FQ_F32, FQ_F16, FQ_BF16}, row stride ldw >= K elements.
- * Wq_out   [N, Kpad] int8 (bits 8) or [N, Kpad/2] uint8 (bits 4), device.
+ * Wq_out   [N, Kpad] int8 (bits 8) or [N, Kpad/2] uint8 (bits 4), device.  bits = FQ_BITS_I4_E3M2 (6): the
+ *          4-bit quantizer with its values stored as E3M2 codes, N * 3 Kpad / 4 bytes in the blocked layout
+ *          described at fq_gemm_i4_e3m2 (Kpad a multiple of 128); likewise for Xq_out of the activation calls.
  * s_w_out  one fp32, device.
  * workspace  fq_weights_workspace_bytes(K, Kpad) bytes, device, 16-byte aligned; contents undefined after.
  * ------------------------------------------------------------------------------------------- */
@@ -291,7 +293,8 @@ int fq_bmm_i4(const uint8_t* Aq, const uint8_t* Bq, int batch, int M, int N, int
 
 /* ---------------------------------------------------------------------------------------------
  * fq_linear — the end-to-end inference call: fq_flatten_quant_act followed by fq_gemm_i8 /
- * fq_gemm_i4 on one stream.  Wq / s_w come from fq_flatten_weights with the same map and bits.
+ * fq_gemm_i4 (fq_gemm_i4_e3m2 for bits = FQ_BITS_I4_E3M2) on one stream.  Wq / s_w come from
+ * fq_flatten_weights with the same map and bits.
  * workspace  fq_linear_workspace_bytes(M, K, Kpad, bits) bytes, device, 16-byte aligned; holds
  *            the quantized activation, the per-slot multipliers and s_x.
  * ------------------------------------------------------------------------------------------- */
