@@ -331,9 +331,9 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)
  *   3: as 0 with 64-byte k-stages        4: as 0 with 4 waves (128x128 per wave)
  *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies
- *   11: INT8 and bf16 only: 256x256 tile, 4 waves with 128x128 wave tiles (one wave per SIMD), two stage buffers,
- *      LDS reads and copies dealt out per MFMA slot.  Measured 12-20 % slower than 7: with two 64 KiB buffers a
- *      stage's copies are issued less than one stage before they are needed.
+ *   11: INT8 and bf16 only, rows of whole 128-byte stages only (FQ_ERR_SHAPE otherwise): 256x256 tile, 4 waves
+ *      with 128x128 wave tiles (one wave per SIMD), two stage buffers, LDS reads and copies dealt out per
+ *      MFMA slot.  Measured +2 % for bf16 (its default for large problems with such rows), -3..-5 % for INT8.
  * fq_gemm_i4_e3m2 has two kernels of its own, both with 256x256 tiles: variant 0 = 8 waves in the ping-pong
  * schedule (wave tile 128x64); any other value = 4 waves with 128x128 wave tiles, LDS reads interleaved
  * between the MFMAs (the default).

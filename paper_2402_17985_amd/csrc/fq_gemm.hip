@@ -788,10 +788,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
 // sits before the last k-slice of a stage, when every wave holds that slice in registers: it frees the
 // stage's buffer for those copies and publishes the next stage (each wave has waited for its own
 // copies), and the last slice's MFMAs overlap the first reads of the next stage.
-// Measured 12-20 % slower than the ping-pong kernel (INT8 2.1 against 2.4 POP/s, 2.6 against 3.2 on zero
-// operands): two 64 KiB buffers are all that fits, so a stage's copies start only three k-slices before
-// they are waited for.  The 6-bit kernel of the same shape (48 KiB stages, ring of three) does not have
-// that limit.  Selectable as variant 11.
+// Rows must be whole 128-byte stages (checked at launch): a per-copy choice between the row and the zero
+// chunk, as the ping-pong kernel makes once per stage, costs this kernel 15 % when it sits between the MFMAs.
+// Measured against the ping-pong kernel: bf16 +2 % (the default for large bf16 problems with such rows),
+// INT8 -3..-5 % on live data and -10 % on zero operands (not used by default): per k-stage it is as fast
+// or slightly faster (1.09 against 1.10 us per 128-byte stage of a tile at full clock), but its fixed cost
+// per tile is 5 us higher -- the integer epilogue spills with 256 accumulators.  Selectable as variant 11.
 template <int MODE, int BM, int BN>
 __device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                                const uint8_t* __restrict__ B, int M, int N, int rowbytes,
@@ -842,8 +844,7 @@ __device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, co
         const uint8_t* g = (isA ? A : B) + kb;
         const uint32_t off = isA ? offA[j] : offB[j];
         const uint32_t dst = (isA ? sA : sA + BM * BKB) + j * NW * 1024;
-        if (stage_index < nk_full) dma16(g, off, dst);
-        else dma16_addr((kb + dchunk * 16 < rowbytes) ? g + off : zero16, dst);
+        dma16(g, off, dst);                      // whole stages only: rowbytes is a multiple of BKB (checked at launch)
     };
     auto issue_all = [&](int stage_index) {
 #pragma unroll
@@ -899,10 +900,15 @@ __device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, co
     typedef std::true_type yes;
     typedef std::false_type no;
 
+    // both buffers are free: issue the first two stages together, wait for the first
     issue_all(0);
-    __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
+    if (nk > 1) {
+        issue_all(1);
+        __builtin_amdgcn_s_waitcnt((LPS & 0xf) | ((LPS >> 4) << 14) | 0x0070);     // vmcnt(LPS) lgkmcnt(0)
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0070);          // vmcnt(0) lgkmcnt(0)
+    }
     __syncthreads();
-    if (nk > 1) issue_all(1);
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_op(smem, 0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
@@ -1544,6 +1550,7 @@ int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const 
     if constexpr (MODE == MODE_I8 || MODE == MODE_BF16) {
         if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
             return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
+        if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variant 11 needs rows of whole 128-byte stages");
         auto kern = gemm_wide_kernel<MODE>;
         constexpr int smem = 2 * 512 * 128;
         static bool attr_set = false;
@@ -1583,6 +1590,8 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         // k-slices per phase and spill, so they keep two k-slices per phase (7), as do reductions of
         // only a few k-stages (attention's Q K^T)
         v = (big_tiles >= 192 && N > 128) ? ((MODE == MODE_I4 && rowbytes >= 512) ? 10 : 7) : 6;
+        // bf16 with rows of whole 128-byte stages: the four-wave kernel (measured +2 %)
+        if (MODE == MODE_BF16 && v == 7 && rowbytes % 128 == 0 && bt.count == 1) v = 11;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);

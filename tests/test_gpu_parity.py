@@ -245,10 +245,10 @@ def test_linear_is_deterministic():
 # ------------------------------------------------------------------------------------------
 # bf16 baseline GEMM
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", [0, 2, 11])
-def test_gemm_bf16_baseline(variant):
+@pytest.mark.parametrize("variant,K", [(0, 1032), (2, 1032), (11, 1024), (11, 192)])
+def test_gemm_bf16_baseline(variant, K):
     rng = np.random.default_rng(9)
-    M, N, K = 300, 260, 1032
+    M, N = 300, 260
     Xs, Xf = WL.round_to_dtype(rng.standard_normal((M, K), dtype=np.float32), "bf16")
     Ws, Wf = WL.round_to_dtype(rng.standard_normal((N, K), dtype=np.float32) / np.float32(np.sqrt(K)), "bf16")
     Y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
@@ -259,8 +259,24 @@ def test_gemm_bf16_baseline(variant):
     finally:
         fq.fq_gemm_select(-1)
     ref = Xf.astype(np.float64) @ Wf.astype(np.float64).T
-    # fp32 accumulation of K = 1032 products, then one bf16 rounding
+    # fp32 accumulation of K products, then one bf16 rounding
     assert rel_err(bf16_to_f64(Y), ref).max() <= 2.0 ** -8 + 1e-4
+
+
+def test_gemm_bf16_baseline_large_default():
+    """A problem large enough (210 tiles of 256 x 256, ragged edges, half-height tail) for the automatic choice
+    to take the large-problem kernel; sampled rows against the float64 product."""
+    rng = np.random.default_rng(10)
+    M, N, K = 15 * 256 - 30, 14 * 256 - 9, 256
+    Xs, Xf = WL.round_to_dtype(rng.standard_normal((M, K), dtype=np.float32), "bf16")
+    Ws, Wf = WL.round_to_dtype(rng.standard_normal((N, K), dtype=np.float32) / np.float32(np.sqrt(K)), "bf16")
+    Y = torch.zeros((M, N + 1), dtype=torch.bfloat16, device=DEV)
+    fq.fq_gemm_bf16(to_dev(Xs, "bf16"), to_dev(Ws, "bf16"), Y[:, :N])
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([rng.integers(0, M, 60), [0, M - 1, 255, 256, 3583, 3584]]))
+    ref = Xf[rows].astype(np.float64) @ Wf.astype(np.float64).T
+    assert rel_err(bf16_to_f64(Y[torch.from_numpy(rows).to(DEV)][:, :N]), ref).max() <= 2.0 ** -8 + 1e-4
+    assert not Y[:, N:].any()
 
 
 # ------------------------------------------------------------------------------------------
@@ -604,13 +620,13 @@ def test_gemm_four_wave_kernel_int8():
     rng = np.random.default_rng(1100)
     fq.fq_gemm_select(11)
     try:
-        for (M, N, Kpad) in [(300, 520, 416), (257, 129, 1056), (1, 1, 32), (33, 700, 160), (512, 256, 128), (70, 41, 256),
-                             (17 * 256 - 20, 16 * 256 - 7, 160)]:
+        for (M, N, Kpad) in [(300, 520, 384), (257, 129, 1152), (1, 1, 128), (33, 700, 256), (512, 256, 128), (70, 41, 640),
+                             (17 * 256 - 20, 16 * 256 - 7, 256)]:
             Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
             assert np.array_equal(_gemm_acc(Xq, Wq, 8), O.gemm_i32(Xq, Wq)), (M, N, Kpad)
         lo = -128
-        Xq = np.full((40, 26016), lo, np.int8)
-        Wq = np.full((70, 26016), lo, np.int8)
+        Xq = np.full((40, 26112), lo, np.int8)
+        Wq = np.full((70, 26112), lo, np.int8)
         Wq[1::2] = 127
         assert np.array_equal(_gemm_acc(Xq, Wq, 8), O.gemm_i32(Xq, Wq))
         # epilogue: bf16 with bias, padded row stride
@@ -629,7 +645,7 @@ def test_gemm_four_wave_kernel_int8():
         assert (np.abs(got - O.dequant_bias(acc, s_x, s_w, bias)) / denom).max() <= 2.0 ** -8
         assert (Ybuf[:, N:].float() == 7.0).all()
         # batched
-        Aq, Bq = _bmm_operands(7, 3, 260, 300, 192, 8)
+        Aq, Bq = _bmm_operands(7, 3, 260, 300, 256, 8)
         Y = torch.full((3, 260, 300), -1, dtype=torch.int32, device=DEV)
         fq.fq_bmm_i8(_to_dev_q(Aq, 8), _to_dev_q(Bq, 8), None, None, Y)
         torch.cuda.synchronize()
@@ -638,12 +654,15 @@ def test_gemm_four_wave_kernel_int8():
         fq.fq_gemm_select(-1)
 
 
-def test_gemm_four_wave_kernel_rejects_nibbles():
+def test_gemm_four_wave_kernel_rejects_nibbles_and_partial_stages():
     fq.fq_gemm_select(11)
     try:
         Xq = torch.zeros((4, 16), dtype=torch.uint8, device=DEV)
         Y = torch.zeros((4, 4), dtype=torch.int32, device=DEV)
         with pytest.raises(fq.FqError, match="FQ_ERR_RANGE"):
             fq.fq_gemm_i4(Xq, Xq, None, None, Y)
+        X8 = torch.zeros((4, 160), dtype=torch.int8, device=DEV)          # 160-byte rows: a partial second stage
+        with pytest.raises(fq.FqError, match="FQ_ERR_SHAPE"):
+            fq.fq_gemm_i8(X8, X8, None, None, Y)
     finally:
         fq.fq_gemm_select(-1)
