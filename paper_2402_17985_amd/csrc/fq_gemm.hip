@@ -1,5 +1,6 @@
 // LDS-tiled MFMA GEMMs for gfx950: INT8, packed INT4 (widened to INT8 in registers) and the
-// bf16 baseline, from one kernel template.
+// bf16 baseline from one kernel template, and the 4-bit GEMM on the 6-bit matrix pipe (operands
+// stored as E3M2 codes; its own kernels and layout, described where they are defined).
 //
 // arXiv 2402.17985 Sec. 5.1: the quantized linear layer is an INT8 / INT4 GEMM with int32
 // accumulation whose result is scaled back by s_x * s_w (the inverse of Eq. 1); Table 5 compares
@@ -22,7 +23,7 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on
 // a contiguous band of tiles, walked in groups of GROUP_M tile-rows for L2 reuse.
 //
-// Two kernels:
+// Kernels of the int8 / bf16 family:
 //   gemm_dma_kernel   global -> LDS directly (global_load_lds_dwordx4: a wave fills one contiguous
 //                     1 KiB block of the stage per instruction, each lane fetching the global chunk
 //                     that belongs at its LDS position), stage t+1 in flight while stage t is
@@ -32,7 +33,10 @@
 //                     the ping-pong schedule one workgroup per CU walks its tiles and fetches the next
 //                     tile's first stage while it stores the current one.  Batched products put the
 //                     batch index in the grid's y dimension.
+//   gemm_wide_kernel  INT8 and bf16: four waves with 128 x 128 wave tiles, reads and copies dealt out
+//                     per MFMA slot (default for large bf16 problems).
 //   gemm_reg_kernel   global -> registers -> LDS, 128x128 tile; a selectable variant.
+// 6-bit pipe: gemm_f6_wide_kernel (four waves, the default) and gemm_f6_kernel (ping-pong).
 // This file is compiled once per operand mode (see the end of the file).
 #include <type_traits>
 
