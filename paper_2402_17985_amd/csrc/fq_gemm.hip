@@ -272,7 +272,9 @@ __device__ __forceinline__ void store_tile_via_lds(acc_t (&acc)[FM][FN], int row
     }
 }
 
-template <int MODE, int FM, int FN, int CH = FM, typename acc_t>
+// ONLY_BF16: the caller guarantees y_dtype == FQ_BF16 and no bias, and only that path is compiled (a kernel
+// that carries every output type keeps more live state across its main loop and spills in the epilogue).
+template <int MODE, int FM, int FN, int CH = FM, bool ONLY_BF16 = false, typename acc_t>
 __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int col0, int M, int N,
                                            const float* __restrict__ s_x, const float* __restrict__ s_w,
                                            void* __restrict__ Y, int y_dtype, int ldy, uint8_t* stage = nullptr,
@@ -285,6 +287,12 @@ __device__ __forceinline__ void store_tile(acc_t (&acc)[FM][FN], int row0, int c
         if (staged) store_tile_via_lds<MODE, FQ_BF16, FM, FN, false, CH>(acc, row0, col0, 1.0f, Y, ldy, stage);
         else store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, 1.0f, Y, ldy, fast);
     } else {
+        if constexpr (ONLY_BF16) {
+            const float scale = (*s_x) * (*s_w);
+            if (staged) store_tile_via_lds<MODE, FQ_BF16, FM, FN, false, CH>(acc, row0, col0, scale, Y, ldy, stage);
+            else store_tile_as<MODE, FQ_BF16, FM, FN>(acc, row0, col0, M, N, scale, Y, ldy, fast);
+            return;
+        }
         if (y_dtype == FQ_I32) {
             store_tile_as<MODE, FQ_I32, FM, FN>(acc, row0, col0, M, N, 1.0f, Y, ldy, fast);
             return;
@@ -1146,7 +1154,7 @@ __device__ __forceinline__ void gemm_f6_tile(uint8_t* smem, int m0, int n0, cons
 // its second slice: it publishes stage kt+1 (each wave waited for its own copies), frees stage kt's
 // buffer for the copy of stage kt+3, and lets the MFMAs of the second slice overlap the first reads
 // of stage kt+1.
-template <int BM, int BN>
+template <int BM, int BN, bool ONLY_BF16>
 __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                                   const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                                   const float* __restrict__ s_x, const float* __restrict__ s_w,
@@ -1312,12 +1320,13 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
     }
     __syncthreads();                                // every wave is past its last LDS operand read
 
-    store_tile<MODE_F6, FM, FN, 2>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+    store_tile<MODE_F6, FM, FN, 2, ONLY_BF16>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
                                    smem + wave * (64 * TN * 2), bias);
 }
 
 // Workgroups [0, n_main) compute 256 x 256 tiles; a last, partly filled round of at most half the CUs is
 // computed as 128 x 256 halves by workgroups [n_main, n_main + 2 n_tail), so that it takes about half as long.
+template <bool ONLY_BF16>
 __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B,
                                                            int M, int N, int rowbytes, const float* __restrict__ s_x,
                                                            const float* __restrict__ s_w, void* __restrict__ Y,
@@ -1332,12 +1341,12 @@ __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __rest
     const int v = blockIdx.x;
     if (v < n_main) {
         tile_of_workgroup(v, n_main, tiles_m, tiles_n, tile_m, tile_n);
-        gemm_f6_wide_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+        gemm_f6_wide_tile<256, 256, ONLY_BF16>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
                                     bt.bias);
     } else {
         const int t = v - n_main;
         tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
-        gemm_f6_wide_tile<128, 256>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y,
+        gemm_f6_wide_tile<128, 256, ONLY_BF16>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y,
                                     y_dtype, ldy, bt.bias);
     }
 }
@@ -1635,8 +1644,9 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long tiles = (long long)tiles_m * tiles_n;
     if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
-    static bool attr_set_wide = false;
-    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel), smem, attr_set_wide)) return rc;
+    static bool attr_set_wide = false, attr_set_wide_bf16 = false;
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel<false>), smem, attr_set_wide)) return rc;
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel<true>), smem, attr_set_wide_bf16)) return rc;
     if (forced_gemm_variant() != 0) {
         // a last round that would occupy at most half of the CUs is run as half-height tiles instead
         const int cus = compute_units();
@@ -1646,7 +1656,9 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
             n_tail = r;
             n_main = (int)tiles - r;
         }
-        gemm_f6_wide_kernel<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
+        // the common case (bf16 output, no bias) has an instantiation with that epilogue only
+        auto kern = (y_dtype == FQ_BF16 && !bt.bias) ? gemm_f6_wide_kernel<true> : gemm_f6_wide_kernel<false>;
+        kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
             static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
             tiles_m, tiles_n, n_main, bt);
     }
