@@ -323,7 +323,7 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *   7: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the
  *      two waves of a SIMD alternate LDS-read and MFMA phases, two MFMA k-steps per phase
  *   10: as 7 with phases twice as long (four MFMA k-steps per phase).  Large problems use 10 for INT4
- *      and 7 for INT8 and bf16; one workgroup per CU then walks its tiles and fetches the first stage
+ *      and 7 (or 11, see there) for INT8 and bf16; one workgroup per CU then walks its tiles and fetches the first stage
  *      of the next tile before it stores the current one
  *   8: as 7 with one k-slice per phase        9: as 7 with 64-byte k-stages in a ring of 4 buffers
  *   0: as 7 with LDS reads interleaved between the MFMAs and one barrier per stage, placed before the
@@ -333,7 +333,8 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies
  *   11: INT8 and bf16 only, rows of whole 128-byte stages only (FQ_ERR_SHAPE otherwise): 256x256 tile, 4 waves
  *      with 128x128 wave tiles (one wave per SIMD), two stage buffers, LDS reads and copies dealt out per
- *      MFMA slot.  Measured +2 % for bf16 (its default for large problems with such rows), -3..-5 % for INT8.
+ *      MFMA slot.  The default for large INT8 and bf16 problems with such rows and a bf16 output without bias
+ *      (+2 % on live data against 7); other outputs keep 7.
  * fq_gemm_i4_e3m2 has two kernels of its own, both with 256x256 tiles: variant 0 = 8 waves in the ping-pong
  * schedule (wave tile 128x64); any other value = 4 waves with 128x128 wave tiles, LDS reads interleaved
  * between the MFMAs (the default).

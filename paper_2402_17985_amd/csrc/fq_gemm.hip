@@ -360,7 +360,7 @@ __device__ __forceinline__ void mfma_slice(const v4i (&a)[FM], const v4i (&b)[FN
 // =============================================================================================
 // gemm_dma_kernel: direct global -> LDS stages, register double-buffered MFMA operands
 // =============================================================================================
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2, bool ONLY_BF16 = false>
 __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                               const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                               const float* __restrict__ s_x, const float* __restrict__ s_w,
@@ -729,11 +729,11 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
         constexpr int CH_FIT = SHARE / (32 * TN * 2);
         constexpr int CH = CH_FIT >= FM ? FM : (CH_FIT >= 2 ? 2 : CH_FIT);
         static_assert(CH >= 1 && FM % CH == 0, "output staging must fit the wave's share of a stage buffer");
-        store_tile<MODE, FM, FN, CH>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+        store_tile<MODE, FM, FN, CH, ONLY_BF16>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
                                      smem + STAGE + wave * SHARE, bias);
     } else {
         constexpr bool CAN_STAGE = NW * TM * TN * 2 <= NSTAGE * STAGE;
-        store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+        store_tile<MODE, FM, FN, FM, ONLY_BF16>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
                                  CAN_STAGE ? smem + wave * (TM * TN * 2) : nullptr, bias);
     }
 }
@@ -742,7 +742,7 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
 // last, partly filled round of at most half the CUs, those tiles are instead computed as two
 // (BM/2) x BN halves by workgroups [n_main, n_main + 2 * n_tail), so that the last round takes about
 // half as long.
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2, bool ONLY_BF16 = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __restrict__ A,
                                                                 const uint8_t* __restrict__ B, int M, int N,
                                                                 int rowbytes, const float* __restrict__ s_x,
@@ -768,7 +768,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
             const bool has_next = vn < n_main;
             int next_m = 0, next_n = 0;
             if (has_next) tile_of_workgroup(vn, n_main, tiles_m, tiles_n, next_m, next_n);
-            gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
+            gemm_dma_tile<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES, ONLY_BF16>(smem, tile_m * BM, tile_n * BN, A, B, M, N, rowbytes,
                                                                     s_x, s_w, Y, y_dtype, ldy, bt.bias, prefetched,
                                                                     has_next, next_m * BM, next_n * BN);
             prefetched = CAN_PREFETCH && has_next;
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
             if constexpr (BM >= 128 && (BM / 2) % (64 / (BKB / 16) * WM * WN) == 0) {
                 const int t = v - n_main;
                 tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
-                gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>(smem, tile_m * BM + (t & 1) * (BM / 2),
+                gemm_dma_tile<MODE, BM / 2, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES, ONLY_BF16>(smem, tile_m * BM + (t & 1) * (BM / 2),
                                                                             tile_n * BN, A, B, M, N, rowbytes, s_x, s_w,
                                                                             Y, y_dtype, ldy, bt.bias);
             }
@@ -802,11 +802,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
 // copies), and the last slice's MFMAs overlap the first reads of the next stage.
 // Rows must be whole 128-byte stages (checked at launch): a per-copy choice between the row and the zero
 // chunk, as the ping-pong kernel makes once per stage, costs this kernel 15 % when it sits between the MFMAs.
-// Measured against the ping-pong kernel: bf16 +2 % (the default for large bf16 problems with such rows),
-// INT8 -3..-5 % on live data and -10 % on zero operands (not used by default): per k-stage it is as fast
-// or slightly faster (1.09 against 1.10 us per 128-byte stage of a tile at full clock), but its fixed cost
-// per tile is 5 us higher -- the integer epilogue spills with 256 accumulators.  Selectable as variant 11.
-template <int MODE, int BM, int BN>
+// Measured against the ping-pong kernel, in the instantiation that carries the bf16 epilogue only (the
+// generic one spills with 256 accumulators and loses 5 us per tile): per 128-byte stage of a tile both take
+// 1.08-1.11 us at full clock, fixed cost per tile 7-11 us in both; INT8 +2 % and bf16 +2-4 % on live data,
+// INT8 -2..-5 % on zero operands.  It is the default for large INT8 and bf16 problems with such rows and a
+// plain bf16 output; variant 11 selects it for any output.
+template <int MODE, int BM, int BN, bool ONLY_BF16>
 __device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                                const uint8_t* __restrict__ B, int M, int N, int rowbytes,
                                                const float* __restrict__ s_x, const float* __restrict__ s_w,
@@ -944,13 +945,13 @@ __device__ __forceinline__ void gemm_wide_tile(uint8_t* smem, int m0, int n0, co
     stage(kt, no{}, no{});
     __syncthreads();                                 // every wave is past its last LDS operand read
 
-    store_tile<MODE, FM, FN, 2>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
+    store_tile<MODE, FM, FN, 2, ONLY_BF16>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
                                 smem + wave * (64 * TN * 2), bias);
 }
 
 // Workgroups [0, n_main) compute 256 x 256 tiles; a last, partly filled round of at most half the CUs is
 // computed as 128 x 256 halves by workgroups [n_main, n_main + 2 n_tail).
-template <int MODE>
+template <int MODE, bool ONLY_BF16>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, int M,
                                                         int N, int rowbytes, const float* __restrict__ s_x,
                                                         const float* __restrict__ s_w, void* __restrict__ Y, int y_dtype,
@@ -964,12 +965,12 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
     const int v = blockIdx.x;
     if (v < n_main) {
         tile_of_workgroup(v, n_main, tiles_m, tiles_n, tile_m, tile_n);
-        gemm_wide_tile<MODE, 256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+        gemm_wide_tile<MODE, 256, 256, ONLY_BF16>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
                                        bt.bias);
     } else {
         const int t = v - n_main;
         tile_of_logical(n_main + (t >> 1), tiles_m, tiles_n, tile_m, tile_n);
-        gemm_wide_tile<MODE, 128, 256>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w,
+        gemm_wide_tile<MODE, 128, 256, ONLY_BF16>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w,
                                        Y, y_dtype, ldy, bt.bias);
     }
 }
@@ -1501,14 +1502,14 @@ int compute_units()
     return cus;
 }
 
-template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2>
+template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2, bool ONLY_BF16 = false>
 int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
     // the DMA kernel addresses rows with 32-bit byte offsets
     if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
         return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
-    auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES>;
+    auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES, ONLY_BF16>;
     constexpr int smem = NSTAGE * (BM + BN) * BKB;
     static bool attr_set = false;
     if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
@@ -1564,10 +1565,12 @@ int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const 
         if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
             return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
         if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variant 11 needs rows of whole 128-byte stages");
-        auto kern = gemm_wide_kernel<MODE>;
+        // the common case (bf16 output, no bias) has an instantiation with that epilogue only
+        const bool only_bf16 = y_dtype == FQ_BF16 && !bt.bias;
+        auto kern = only_bf16 ? gemm_wide_kernel<MODE, true> : gemm_wide_kernel<MODE, false>;
         constexpr int smem = 2 * 512 * 128;
-        static bool attr_set = false;
-        if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
+        static bool attr_set[2] = {false, false};
+        if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set[only_bf16 ? 1 : 0])) return rc;
         const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
         const long long tiles = (long long)tiles_m * tiles_n;
         if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
@@ -1603,8 +1606,11 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         // k-slices per phase and spill, so they keep two k-slices per phase (7), as do reductions of
         // only a few k-stages (attention's Q K^T)
         v = (big_tiles >= 192 && N > 128) ? ((MODE == MODE_I4 && rowbytes >= 512) ? 10 : 7) : 6;
-        // bf16 with rows of whole 128-byte stages: the four-wave kernel (measured +2 %)
-        if (MODE == MODE_BF16 && v == 7 && rowbytes % 128 == 0 && bt.count == 1) v = 11;
+        // INT8 and bf16 with rows of whole 128-byte stages, bf16 output and no bias (the instantiation with
+        // that epilogue only): the four-wave kernel, measured +2 % on live data
+        if ((MODE == MODE_BF16 || MODE == MODE_I8) && v == 7 && rowbytes % 128 == 0 && bt.count == 1 &&
+            y_dtype == FQ_BF16 && !bt.bias)
+            v = 11;
     }
     switch (v) {
     case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
@@ -1614,10 +1620,17 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 7: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 7:
+        // the large-problem kernels have an instantiation with the plain bf16 epilogue only (no spills)
+        if (MODE != MODE_BF16 && y_dtype == FQ_BF16 && !bt.bias)
+            return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2, true>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+        return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 10: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+    case 10:
+        if (MODE != MODE_BF16 && y_dtype == FQ_BF16 && !bt.bias)
+            return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4, true>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
+        return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 11: return launch_wide<MODE>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     default: return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
     }
