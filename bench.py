@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of the dominant kernel (the 4-bit GEMM, average of its two launches per step) for
 # the default workload and kernel choice, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
 # by a plain 1 GiB copy in the same runs: profiles/pmc_traffic_bench_cfg3_m8192.txt.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0, "e3m2"): 7.47e8, ("cfg3,cfg3i8", -1, 0, "nibble"): 5.88e8}
+MEASURED_TRAFFIC_BYTES = {("cfg3,cfg3i8", -1, 0, "e3m2"): 7.17e8, ("cfg3,cfg3i8", -1, 0, "nibble"): 5.83e8}
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA peak (packed INT4 is widened to int8 on chip: same ceiling)
 FP6_PEAK_TFLOPS = 10100.0    # dense 6-bit MFMA peak: the ceiling of the 4-bit layers in E3M2 storage
