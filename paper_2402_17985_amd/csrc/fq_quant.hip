@@ -476,7 +476,7 @@ __global__ __launch_bounds__(256) void flatten_quant_kernel(const void* __restri
 // made of such slots and padding (cflag) is copied from LDS; any other group is gathered from global
 // memory and quantized with its own multipliers.
 template <int DT, int BITS>
-__global__ __launch_bounds__(256) void flatten_quant_rows_kernel(const void* __restrict__ Xv, int M, int K, int ld,
+__global__ __launch_bounds__(BITS == 6 ? 512 : 256) void flatten_quant_rows_kernel(const void* __restrict__ Xv, int M, int K, int ld,
                                                                  const int32_t* __restrict__ src,
                                                                  const float* __restrict__ mslot,
                                                                  const uint8_t* __restrict__ gflag, int Kpad, int R,
@@ -735,8 +735,27 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
             const int nthr = 256;
             if (bits == 8)
                 flatten_quant_rows_kernel<DT, 8><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
-            else if (bits == 6)
-                flatten_quant_rows_kernel<DT, 6><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
+            else if (bits == 6) {
+                // Very wide layers (strips cut to two rows or one): the blocked E3M2 layout then gets runs of only
+                // 192 or 96 bytes per block.  A strip twice as high in a 512-thread workgroup with up to 128 KiB of
+                // LDS (one workgroup per CU) measured 11 % faster at K = 22016; at K = 11008 (four rows -> eight)
+                // the same change was 16 % slower, so it stops there.
+                int R6 = R;
+                size_t lds6 = lds;
+                int nthr6 = nthr;
+                if (R <= 2 && (size_t)(2 * R) * kq + tail_src <= 128u * 1024u) {
+                    R6 = 2 * R;
+                    lds6 = (size_t)R6 * kq + tail_src;
+                    nthr6 = 512;
+                    static bool attr = false;
+                    if (!attr) {
+                        hipFuncSetAttribute(reinterpret_cast<const void*>(flatten_quant_rows_kernel<DT, 6>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                        attr = true;
+                    }
+                }
+                flatten_quant_rows_kernel<DT, 6><<<(unsigned)((M + R6 - 1) / R6), nthr6, lds6, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R6, o8);
+            }
             else
                 flatten_quant_rows_kernel<DT, 4><<<nblk, nthr, lds, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R, o8);
             hipError_t e = hipGetLastError();
