@@ -666,3 +666,17 @@ def test_gemm_four_wave_kernel_rejects_nibbles_and_partial_stages():
             fq.fq_gemm_i8(X8, X8, None, None, Y)
     finally:
         fq.fq_gemm_select(-1)
+
+
+def test_gemm_int8_large_default_bf16_output():
+    """272 tiles with whole-stage rows and a plain bf16 output: the automatic choice takes the four-wave kernel in
+    its bf16-only instantiation (with half-height tail tiles); every output against the oracle."""
+    rng = np.random.default_rng(1200)
+    M, N, Kpad = 17 * 256 - 20, 16 * 256 - 7, 256
+    Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
+    Y = torch.zeros((M, N + 7), dtype=torch.bfloat16, device=DEV)
+    fq.fq_gemm_i8(torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV), scalar(0.01), scalar(0.003), Y[:, :N])
+    torch.cuda.synchronize()
+    y_ref = O.dequant(O.gemm_i32(Xq, Wq), np.float32(0.01), np.float32(0.003))
+    assert rel_err(bf16_to_f64(Y[:, :N]), y_ref).max() <= 2.0 ** -8
+    assert not Y[:, N:].any()
