@@ -725,3 +725,81 @@ int fqo_unpack_e3m2(const uint8_t *packed, long long rows, int Kpad, double *out
         }
     return FQO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Dequantize to the layer's output type (the inverse of Eq. 1 applied to the product, Sec. 5.1:
+ * the quantized layer hands a 16-bit floating-point tensor to the next operator).  The value is
+ * defined in fp32, every step rounded once to nearest-even:
+ *     f = fl32( fl32(acc) * fl32(s_x * s_w) )            fl32(acc): the int32 rounded to fp32
+ *     f = fl32( f + bias[n] )                            only when a bias is given
+ *     y = f rounded to the output type: fp32 (unchanged), IEEE half, or bfloat16.
+ * The two 16-bit roundings are written out on the bit pattern of f (no compiler conversion is
+ * relied on).  out_dtype: 0 = fp32 (out is float*), 1 = half, 2 = bfloat16 (out is uint16_t* and
+ * receives the bit patterns).
+ * ---------------------------------------------------------------------------------------- */
+static uint32_t bits_of(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return u;
+}
+
+/* fp32 -> bfloat16 (1 sign, 8 exponent, 7 fraction bits): keep the top 16 bits, round to nearest on
+ * the 16 dropped bits, ties to the even kept pattern.  The carry of a round-up runs into the
+ * exponent, which is what rounding up to the next binade (or to infinity) means. */
+static uint16_t round_to_bf16(float f)
+{
+    uint32_t u = bits_of(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   /* NaN stays NaN */
+    uint32_t kept = u >> 16, dropped = u & 0xffffu;
+    if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u))) kept += 1;
+    return (uint16_t)kept;
+}
+
+/* fp32 -> IEEE half (1 sign, 5 exponent bits with bias 15, 10 fraction bits), nearest-even,
+ * through the value: |f| = m * 2^e is placed on half's grid (spacing 2^(E-10) in the binade 2^E,
+ * E >= -14; spacing 2^-24 below 2^-14) with rint (ties to even in the default rounding mode). */
+static uint16_t round_to_f16(float f)
+{
+    uint32_t u = bits_of(f);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t mag = u & 0x7fffffffu;
+    if (mag > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);        /* NaN */
+    if (mag == 0x7f800000u) return (uint16_t)(sign | 0x7c00u);       /* infinity */
+    double a = fabs((double)f);
+    if (a == 0.0) return sign;
+    int E;
+    (void)frexp(a, &E);                 /* a = x * 2^E with 0.5 <= x < 1, so a lies in [2^(E-1), 2^E) */
+    int binade = E - 1;
+    if (binade < -14) binade = -14;     /* subnormal halves share the spacing of the lowest binade */
+    double spacing = ldexp(1.0, binade - 10);
+    double steps = rint(a / spacing);   /* exact division by a power of two; ties to even */
+    double r = steps * spacing;
+    if (r >= 65520.0) return (uint16_t)(sign | 0x7c00u);             /* beyond the largest half: infinity */
+    /* r is on the grid: rebuild its pattern */
+    if (r < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)steps);               /* subnormal: steps of 2^-24 */
+    int E2;
+    (void)frexp(r, &E2);
+    int e = E2 - 1;                                                   /* r in [2^e, 2^(e+1)) */
+    uint32_t frac = (uint32_t)(r / ldexp(1.0, e - 10)) - 1024u;       /* 10 fraction bits */
+    return (uint16_t)(sign | (uint32_t)((e + 15) << 10) | frac);
+}
+
+int fqo_dequant_out(const int32_t *acc, int rows, int N, float s_x, float s_w, const float *bias /* or NULL */,
+                    int out_dtype, void *out)
+{
+    if (!acc || !out || rows <= 0 || N <= 0 || out_dtype < 0 || out_dtype > 2) return FQO_ERR_ARG;
+    const float scale = s_x * s_w;                       /* one fp32 multiply */
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < rows; ++i)
+        for (int n = 0; n < N; ++n) {
+            size_t at = (size_t)i * N + n;
+            float a = (float)acc[at];                    /* int32 -> fp32, nearest-even */
+            float f = a * scale;                         /* one fp32 multiply (the build forbids contraction) */
+            if (bias) f = f + bias[n];                   /* one fp32 add */
+            if (out_dtype == 0) ((float *)out)[at] = f;
+            else if (out_dtype == 1) ((uint16_t *)out)[at] = round_to_f16(f);
+            else ((uint16_t *)out)[at] = round_to_bf16(f);
+        }
+    return FQO_OK;
+}

@@ -342,6 +342,25 @@ def dequant_bias(acc, s_x, s_w, bias):
     return out
 
 
+def dequant_out(acc, s_x, s_w, out_dtype, bias=None):
+    """The layer's output as stored: fl32(fl32(acc) * fl32(s_x * s_w)) (+ bias, one more fp32 rounding)
+    rounded to nearest-even to out_dtype in {"f32", "f16", "bf16"}.  Returns float32 values for "f32" and
+    the uint16 bit patterns for the two 16-bit types, shaped like acc [rows, N]."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    rows, N = acc.shape
+    code = {"f32": 0, "f16": 1, "bf16": 2}[out_dtype]
+    out = np.empty((rows, N), dtype=np.float32 if code == 0 else np.uint16)
+    pb = None
+    if bias is not None:
+        bias = _f32(bias)
+        assert bias.shape == (N,)
+        pb = _p(bias, ctypes.c_float)
+    rc = lib().fqo_dequant_out(_p(acc, ctypes.c_int32), rows, N, ctypes.c_float(s_x), ctypes.c_float(s_w), pb, code,
+                               out.ctypes.data_as(ctypes.c_void_p))
+    _check(rc, "fqo_dequant_out")
+    return out
+
+
 def pack_e3m2(q):
     """4-bit values as packed 6-bit E3M2 codes: int8 [rows, Kpad] -> uint8 [rows, Kpad * 3 / 4]."""
     q = np.ascontiguousarray(q, dtype=np.int8)
