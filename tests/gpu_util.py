@@ -35,3 +35,12 @@ def rel_err(got: np.ndarray, ref: np.ndarray):
     outputs near zero do not blow the ratio up."""
     floor = 1e-3 * float(np.sqrt(np.mean(ref.astype(np.float64) ** 2))) + 1e-300
     return np.abs(got - ref) / np.maximum(np.abs(ref), floor)
+
+
+def bits16(t) -> np.ndarray:
+    """Bit patterns of a 2-byte floating-point device tensor (bf16 or half) as uint16."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def bits32(t) -> np.ndarray:
+    return t.contiguous().view(torch.int32).cpu().numpy().view(np.uint32)

@@ -14,7 +14,7 @@ import torch
 import fq_workloads as WL
 import paper_2402_17985_amd as fq
 from oracle import fq_oracle as O
-from tests.gpu_util import DEV, bf16_to_f64, rel_err, to_dev
+from tests.gpu_util import DEV, bf16_to_f64, bits16, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -76,7 +76,13 @@ def _check_layer(cfg_name, idx, n_sample_rows=256, n_sample_cols=256, freivalds=
     Y = lay.forward(Xd, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
     y_o = O.dequant(acc_o, s_x_o, s_w_o)
-    assert rel_err(bf16_to_f64(Y[torch.from_numpy(rows).to(DEV)]), y_o).max() <= 2.0 ** -8
+    Yrows = Y[torch.from_numpy(rows).to(DEV)]
+    assert rel_err(bf16_to_f64(Yrows), y_o).max() <= 2.0 ** -8           # sanity against the unrounded value
+    # the stored bf16 bits of the timed kernel (bf16 output, no bias) equal the oracle's rounded output
+    assert np.array_equal(bits16(Yrows), O.dequant_out(acc_o, s_x_o, s_w_o, "bf16"))
+    acc_cols = O.gemm_i32(Xq_o, Wq_o[cols_s])
+    assert np.array_equal(bits16(Y[:, torch.from_numpy(cols_s).to(DEV)]), O.dequant_out(acc_cols, s_x_o, s_w_o, "bf16"))
+    print("[fullsize]   bf16 output bits equal the oracle's on the sampled rows and columns", flush=True)
 
 
 def test_cfg2_full():
@@ -96,6 +102,27 @@ def test_cfg2_full():
 @pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg3i8", 0)])
 def test_benchmark_layers_full_size(cfg, idx):
     _check_layer(cfg, idx)
+
+
+@pytest.mark.parametrize("cfg,idx,e3m2", [("cfg2", 0, False), ("cfg3", 0, False), ("cfg3", 1, False), ("cfg3i8", 0, False),
+                                          ("cfg3", 0, True), ("cfg3", 1, True)])
+def test_timed_call_stores_the_oracles_bf16_bits_whole_matrix(cfg, idx, e3m2):
+    """The call bench.py times (fq_linear, dynamic scale, bf16 output, automatic kernel choice) against the
+    oracle's whole layer, every output element: the stored bf16 bit patterns are equal."""
+    L = WL.make_layer(WL.CONFIGS[cfg], idx)
+    sp = L.spec
+    print(f"[fullsize] whole-matrix bf16 bits: {cfg}.{sp.name} M={sp.M} K={sp.K} N={sp.N} bits={sp.bits} e3m2={e3m2}", flush=True)
+    lay = fq.FqLinear(to_dev(L.W_store, sp.w_dtype), L.chmax, L.T, E3 if e3m2 else sp.bits)
+    Y = lay.forward(to_dev(L.X_store, sp.x_dtype))
+    torch.cuda.synchronize()
+    assert Y.dtype == torch.bfloat16
+    got = bits16(Y)
+    del Y
+    src, rep, kp, kpad = O.plan(L.chmax, L.T, 128 if (sp.bits == 8 or e3m2) else 256)
+    Wq_o, s_w_o = O.flatten_weights(L.W, src, sp.bits)
+    acc_o, _, s_x_o = O.linear(L.X, src, rep, Wq_o, s_w_o, sp.bits, want_y=False)
+    print("[fullsize]   oracle layer done", flush=True)
+    assert np.array_equal(got, O.dequant_out(acc_o, s_x_o, s_w_o, "bf16"))
 
 
 @pytest.mark.parametrize("cfg,idx", [("cfg3", 0), ("cfg3", 1), ("cfg4", 2), ("cfg5", 3), ("cfgP", 1)])

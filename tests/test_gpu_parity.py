@@ -2,7 +2,9 @@
 
 Bars (arXiv 2402.17985 fixes the arithmetic; the tolerances follow from it):
   - flatten maps, quantized INT8 / packed INT4 tensors, scales and int32 accumulators: bit-exact;
-  - dequantized outputs against the oracle's float64 y = acc * s_x * s_w:
+  - dequantized outputs: the stored fp32 / half / bfloat16 bit patterns equal the oracle's rounded output
+    fl32(fl32(acc) * fl32(s_x * s_w)) (+ bias), rounded to nearest-even to the output type: bit-exact;
+  - and, as a sanity line, against the oracle's unrounded float64 y = acc * s_x * s_w:
       fp32 out  <= 1e-6 relative  (fl32(acc), fl32(s_x*s_w) and one multiply: 3 roundings of 2^-24),
       fp16 out  <= 1e-3 relative  (half ulp 4.9e-4 on top of the above),
       bf16 out  <= 2^-8 relative  (bf16 keeps 8 significand bits: its own rounding is up to 2^-9;
@@ -15,7 +17,7 @@ import torch
 import fq_workloads as WL
 import paper_2402_17985_amd as fq
 from oracle import fq_oracle as O
-from tests.gpu_util import DEV, bf16_to_f64, bytes_ws, dev_i32, rel_err, scalar, to_dev
+from tests.gpu_util import DEV, bf16_to_f64, bits16, bits32, bytes_ws, dev_i32, rel_err, scalar, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -117,6 +119,56 @@ def test_flatten_quant_act_strided_rows_zero_input_and_bad_map():
     assert np.array_equal(got, want)
 
 
+def _synthetic_layer(seed, M, K, dtype, n_out, factor, T_mult):
+    """A layer's activation side built directly (shapes the workload table has no entry for)."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    idx = rng.choice(K, n_out, replace=False)
+    X[:, idx] *= np.float32(factor)
+    store, Xf = WL.round_to_dtype(X, dtype)
+    chmax = np.abs(Xf).max(axis=0).astype(np.float32)
+    T = float(np.float32(T_mult * np.median(chmax)))
+    return WL.Layer(WL.LayerSpec("synthetic", M, K, 8, 8, dtype, dtype), store, Xf, None, None, chmax, T)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("K,n_out", [(8, 1), (66000, 40)])
+def test_flatten_quant_act_general_kernel_narrow_and_very_wide(K, n_out, bits):
+    """K < 16 and a layer too wide for the row-strip kernel's LDS budget: the equal split through the general
+    one-thread-per-16-slots kernel, dynamic scale, byte for byte."""
+    L = _synthetic_layer(40 + K % 7, 4, K, "bf16", n_out, 30.0, 3.0)
+    src, rep, kp, kpad = fq.fq_flatten_plan(L.chmax, L.T)
+    assert kpad > K and kpad < 131072
+    got, s_x = _gpu_flatten_quant(L, src, rep, bits)
+    want, s_x_o = _oracle_flatten_quant(L, src, rep, bits)
+    assert s_x == s_x_o
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dtype,K,ld", [("bf16", 1004, 1008), ("f32", 202, 204), ("f16", 1004, 1008)])
+def test_flatten_quant_act_ragged_last_column_group(dtype, K, ld, bits):
+    """K not a multiple of the 16-byte vector width with an aligned row stride: the absmax kernel's last column
+    group is read element by element.  The outliers sit in that ragged tail so that it decides the scale."""
+    rng = np.random.default_rng(50 + K)
+    M = 300
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    X[:, K - 1] *= 40.0
+    X[:, K - 3] *= 17.0
+    store, Xf = WL.round_to_dtype(X, dtype)
+    chmax = np.abs(Xf).max(axis=0).astype(np.float32)
+    T = float(np.float32(3.0 * np.median(chmax)))
+    L = WL.Layer(WL.LayerSpec("ragged", M, K, 8, 8, dtype, dtype), store, Xf, None, None, chmax, T)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
+    buf = torch.zeros((M, ld), dtype=tdt, device=DEV)
+    buf[:, :K] = to_dev(store, dtype)
+    src, rep, kp, kpad = fq.fq_flatten_plan(chmax, T)
+    got, s_x = _gpu_flatten_quant(L, src, rep, bits, X_dev=buf[:, :K])
+    want, s_x_o = _oracle_flatten_quant(L, src, rep, bits)
+    assert s_x == s_x_o
+    assert np.array_equal(got, want)
+
+
 # ------------------------------------------------------------------------------------------
 # weights (offline)
 # ------------------------------------------------------------------------------------------
@@ -195,6 +247,11 @@ def test_gemm_dequant_epilogue(ydt, tol):
     got = Ybuf[:, :N].float().cpu().numpy().astype(np.float64)
     assert rel_err(got, ref).max() <= tol
     assert (Ybuf[:, N:].float() == 7.0).all()                # nothing written beyond column N
+    # the stored bit patterns are the oracle's rounded output
+    name = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}[ydt]
+    exact = O.dequant_out(O.gemm_i32(Xq, Wq), s_x, s_w, name)
+    stored = bits32(Ybuf[:, :N]) if ydt == torch.float32 else bits16(Ybuf[:, :N])
+    assert np.array_equal(stored, exact.view(np.uint32) if ydt == torch.float32 else exact)
 
 
 # ------------------------------------------------------------------------------------------
@@ -680,3 +737,92 @@ def test_gemm_int8_large_default_bf16_output():
     y_ref = O.dequant(O.gemm_i32(Xq, Wq), np.float32(0.01), np.float32(0.003))
     assert rel_err(bf16_to_f64(Y[:, :N]), y_ref).max() <= 2.0 ** -8
     assert not Y[:, N:].any()
+
+
+# ------------------------------------------------------------------------------------------
+# the kernels the benchmark times: large problems, plain bf16 output -> the instantiations that carry the
+# bf16 epilogue only.  Their stored bits against the oracle's rounded output, element by element.
+# ------------------------------------------------------------------------------------------
+def _q_operands(rng, M, N, Kpad, storage):
+    qbits = 8 if storage == 8 else 4
+    Xq, Wq = _rand_q(rng, M, Kpad, qbits), _rand_q(rng, N, Kpad, qbits)
+    if storage == 8:
+        return Xq, Wq, torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV)
+    if storage == 4:
+        return Xq, Wq, torch.from_numpy(O.pack_i4(Xq)).to(DEV), torch.from_numpy(O.pack_i4(Wq)).to(DEV)
+    return Xq, Wq, torch.from_numpy(O.pack_e3m2_blocked(Xq)).to(DEV), torch.from_numpy(O.pack_e3m2_blocked(Wq)).to(DEV)
+
+
+@pytest.mark.parametrize("storage,Kpad", [(8, 512), (8, 416), (4, 1024), (4, 512), (6, 384)])
+def test_large_problem_kernels_store_the_oracles_bf16_bits(storage, Kpad):
+    """272 ragged tiles of 256 x 256 (a second round with half-height tail tiles on a 256-CU device), bf16 output,
+    no bias, automatic kernel choice: INT8 with whole 128-byte stages -> the four-wave kernel, with a partial last
+    stage -> the ping-pong kernel; nibbles with long / short rows -> long / short phases; E3M2 -> the four-wave
+    6-bit kernel; each in its bf16-only instantiation."""
+    rng = np.random.default_rng(7000 + 10 * storage + Kpad)
+    M, N = 17 * 256 - 20, 16 * 256 - 7
+    Xq, Wq, Xd, Wd = _q_operands(rng, M, N, Kpad, storage)
+    s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+    Y = torch.zeros((M, N + 7), dtype=torch.bfloat16, device=DEV)      # rows of Y on 16-byte boundaries
+    if storage == 8:
+        fq.fq_gemm_i8(Xd, Wd, scalar(s_x), scalar(s_w), Y[:, :N])
+    elif storage == 4:
+        fq.fq_gemm_i4(Xd, Wd, scalar(s_x), scalar(s_w), Y[:, :N])
+    else:
+        fq.fq_gemm_i4_e3m2(Xd, Wd, scalar(s_x), scalar(s_w), None, Y[:, :N])
+    torch.cuda.synchronize()
+    acc = O.gemm_i32(Xq, Wq)
+    assert np.array_equal(bits16(Y[:, :N]), O.dequant_out(acc, s_x, s_w, "bf16"))
+    assert not Y[:, N:].any()
+
+
+@pytest.mark.parametrize("storage,Kpad", [(8, 384), (4, 768), (6, 256)])
+def test_exactly_representable_outputs_through_the_bf16_only_kernels(storage, Kpad):
+    """Scales of 1 and sparse operands in {-1, 0, 1}: every accumulator has magnitude <= 256 and is a bf16 value
+    itself, so the stored output must equal the integer accumulator exactly -- a wrong or dropped k-slice in any
+    tile shows as a wrong integer."""
+    rng = np.random.default_rng(7100 + storage)
+    M, N = 17 * 256 - 20, 16 * 256 - 7
+    Xq = (rng.integers(-1, 2, (M, Kpad)) * (rng.random((M, Kpad)) < 0.5)).astype(np.int8)
+    Wq = (rng.integers(-1, 2, (N, Kpad)) * (rng.random((N, Kpad)) < 0.5)).astype(np.int8)
+    if storage == 8:
+        Xd, Wd = torch.from_numpy(Xq).to(DEV), torch.from_numpy(Wq).to(DEV)
+    elif storage == 4:
+        Xd, Wd = torch.from_numpy(O.pack_i4(Xq)).to(DEV), torch.from_numpy(O.pack_i4(Wq)).to(DEV)
+    else:
+        Xd, Wd = torch.from_numpy(O.pack_e3m2_blocked(Xq)).to(DEV), torch.from_numpy(O.pack_e3m2_blocked(Wq)).to(DEV)
+    one = scalar(1.0)
+    Y = torch.zeros((M, N + 7), dtype=torch.bfloat16, device=DEV)
+    call = {8: lambda: fq.fq_gemm_i8(Xd, Wd, one, one, Y[:, :N]), 4: lambda: fq.fq_gemm_i4(Xd, Wd, one, one, Y[:, :N]),
+            6: lambda: fq.fq_gemm_i4_e3m2(Xd, Wd, one, one, None, Y[:, :N])}[storage]
+    call()
+    torch.cuda.synchronize()
+    acc = O.gemm_i32(Xq, Wq)
+    assert np.abs(acc).max() <= 256
+    assert np.array_equal(Y[:, :N].float().cpu().numpy(), acc.astype(np.float32))
+
+
+@pytest.mark.parametrize("storage", [8, 4, 6])
+@pytest.mark.parametrize("ydt", ["bf16", "f16", "f32"])
+def test_biased_and_half_epilogues_store_the_oracles_bits(storage, ydt):
+    """Large-problem kernels in their generic instantiation: bias, half and fp32 outputs, bit for bit."""
+    rng = np.random.default_rng(7200 + storage)
+    M, N, Kpad = 17 * 256 - 20, 16 * 256 - 8, 512
+    Xq, Wq, Xd, Wd = _q_operands(rng, M, N, Kpad, storage)
+    s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+    bias = rng.normal(0, 3.0, N).astype(np.float32)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[ydt]
+    Y = torch.zeros((M, N), dtype=tdt, device=DEV)
+    bd = torch.from_numpy(bias).to(DEV)
+    if storage == 8:
+        fq.fq_gemm_i8_bias(Xd, Wd, scalar(s_x), scalar(s_w), bd, Y)
+    elif storage == 4:
+        fq.fq_gemm_i4_bias(Xd, Wd, scalar(s_x), scalar(s_w), bd, Y)
+    else:
+        fq.fq_gemm_i4_e3m2(Xd, Wd, scalar(s_x), scalar(s_w), bd, Y)
+    torch.cuda.synchronize()
+    exact = O.dequant_out(O.gemm_i32(Xq, Wq), s_x, s_w, ydt, bias=bias)
+    if ydt == "f32":
+        assert np.array_equal(bits32(Y), exact.view(np.uint32))
+    else:
+        assert np.array_equal(bits16(Y), exact)
