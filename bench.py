@@ -250,7 +250,9 @@ def main():
         rows.append(row)
         log("[kernel] " + json.dumps(row))
         if args.sweep:
-            for v in range(4):
+            for v in (2, 6, 7, 10, 11):
+                if v == 11 and (sp.bits != 8 or lay.bits != 8):
+                    continue
                 fq.fq_gemm_select(v)
                 tg = event_time_ms(torch, f_gemm, max(5, args.steps // 2))
                 tb = event_time_ms(torch, f_bf, max(5, args.steps // 2))

@@ -64,7 +64,7 @@ class LayerSpec:
     outlier_fixed: Optional[Tuple[Tuple[int, float], ...]] = None   # explicit (channel, factor)
     factor_range: Tuple[float, float] = (10.0, 100.0)
     t_rule: str = "3xmedian"                 # see threshold()
-    t_value: Optional[float] = None          # the threshold ("value") or the channel budget ("extra")
+    t_value: Optional[float] = None          # the threshold itself (rule "value")
 
 
 @dataclass(frozen=True)
@@ -98,10 +98,12 @@ CONFIGS = {
         for (n, k, nn, b) in (("qkv", 8192, 24576, 8), ("out", 8192, 8192, 8),
                               ("ffn1", 8192, 22016, 4), ("ffn2", 22016, 8192, 4)))),
     # the shape of the paper's operator measurement (Table 5): 8 x 2048 tokens, 4096 -> 4096, about 1024
-    # expanded channels (the threshold is chosen so that the extra channels number at most 1024)
+    # expanded channels.  The thresholds are literals, found once for these seeded tensors as the smallest fp32
+    # value at which the flattened width grows by at most 1024 channels; the full-size test checks that count
+    # through the planner.
     "cfgP": Config("cfgP", 5, tuple(
-        LayerSpec(n, 16384, 4096, 4096, b, outlier_frac=0.01, factor_range=(10.0, 100.0), t_rule="extra", t_value=1024)
-        for (n, b) in (("table5_int8", 8), ("table5_int4", 4)))),
+        LayerSpec(n, 16384, 4096, 4096, b, outlier_frac=0.01, factor_range=(10.0, 100.0), t_rule="value", t_value=t)
+        for (n, b, t) in (("table5_int8", 8, 7.0), ("table5_int4", 4, 6.888889312744141)))),
 }
 
 
@@ -133,21 +135,6 @@ def threshold(rule: str, X: np.ndarray, chmax: np.ndarray, value: Optional[float
         # exceed it (barring ties), i.e. at most 15 % of channels are flattened
         k = int(np.floor(0.15 * K))
         return float(np.sort(chmax)[::-1][k])
-    if rule == "extra":
-        # the smallest threshold (to fp32 resolution, by bisection) whose plan adds at most `value` channels
-        c = chmax.astype(np.float64)
-        extra = lambda t: int(np.sum(np.maximum(np.ceil(c / float(np.float32(t))), 1.0) - 1.0))
-        lo, hi = float(c.max()) / (float(value) + 1.0), float(c.max())
-        for _ in range(60):
-            mid = 0.5 * (lo + hi)
-            if extra(mid) <= value:
-                hi = mid
-            else:
-                lo = mid
-        t = float(np.float32(hi))
-        while extra(t) > value:                      # fp32 rounding of hi may have stepped below the boundary
-            t = float(np.nextafter(np.float32(t), np.float32(np.inf)))
-        return t
     raise ValueError(rule)
 
 

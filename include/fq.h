@@ -61,7 +61,8 @@ enum {
     FQ_ERR_RANGE = 4,      /* T <= 0 or not finite, channel maximum negative / NaN / Inf, size beyond int32 or accumulator bounds */
     FQ_ERR_ALIGN = 5,      /* a device pointer is not 16-byte aligned */
     FQ_ERR_HIP = 6,        /* a HIP launch failed */
-    FQ_ERR_WORKSPACE = 7   /* workspace_bytes smaller than the matching *_workspace_bytes() */
+    FQ_ERR_WORKSPACE = 7,  /* workspace_bytes smaller than the matching *_workspace_bytes() */
+    FQ_ERR_NOMEM = 8       /* a host-side helper could not allocate its temporary (host functions only) */
 };
 
 /* Human-readable reason of the last error on the calling thread ("" if none). */
@@ -119,8 +120,8 @@ int fq_smooth_scales(const float* chmax_x_host, const float* chmax_w_host, int K
 
 /* ---------------------------------------------------------------------------------------------
  * fq_flatten_weights — offline: quantize W per tensor and repeat its channels by the map.
- * Eq. 1 (s_w = max|W| / qmax, qmax = 2^(bits-1) - 1), Eq. 4 (repeat), done "during model
- * quantization" (Fig. 3).
+ * Eq. 1 (s_w = max|W| / qmax, qmax = 2^(bits-1) - 1), Eq. 4 (repeat); an offline step that belongs to
+ * quantizing the model, not to inference (Fig. 3).
  *
  *   m_w = fl32(qmax / max|W|) (quotient in float64),  Wq[n,j] = clamp(rne(W[n,j] * m_w), qmin, qmax),
  *   Wq_out[n,p] = Wq[n, src_idx[p]], 0 in padding slots; bits = 4 packs two slots per byte.
@@ -211,7 +212,9 @@ int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx,
  *
  * fq_gemm_i4 takes both operands packed two per byte ([M, Kpad/2], [N, Kpad/2]); they stay
  * packed in HBM and LDS and are widened to int8 in registers (gfx950 has no 4-bit MFMA).
- * M, N >= 1 arbitrary; Kpad a multiple of 32 with Kpad * 128 * 128 < 2^31.
+ * M, N >= 1; Kpad a multiple of 32 with Kpad * 128 * 128 < 2^31; each quantized operand smaller than
+ * 4 GiB (M, N times the bytes of a quantized row; FQ_ERR_RANGE otherwise: rows are addressed with 32-bit
+ * byte offsets).
  * s_x, s_w  device scalars read by the kernel (no host synchronization).
  * Y         device, row stride ldy >= N elements.  2-byte outputs leave fastest when Y is 128-byte aligned
  *           and ldy is a multiple of 64 elements (whole cache lines per row segment).
@@ -318,26 +321,20 @@ size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits);
 int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * fq_gemm_select — tuning hook for benchmarks: force the kernel variant used by fq_gemm_i8 /
- * fq_gemm_i4 / fq_gemm_bf16 / fq_linear (process-wide).  -1 (default) = chosen from the shape.
- *   7: 256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the
- *      two waves of a SIMD alternate LDS-read and MFMA phases, two MFMA k-steps per phase
- *   10: as 7 with phases twice as long (four MFMA k-steps per phase).  Large problems use 10 for INT4
- *      and 7 (or 11, see there) for INT8 and bf16; one workgroup per CU then walks its tiles and fetches the first stage
- *      of the next tile before it stores the current one
- *   8: as 7 with one k-slice per phase        9: as 7 with 64-byte k-stages in a ring of 4 buffers
- *   0: as 7 with LDS reads interleaved between the MFMAs and one barrier per stage, placed before the
- *      stage's last k-slice          1: as 0 with the barrier at the end of the stage
- *   2: 128x128 tile, 64-byte k-stages, 4 waves, staged through registers (the small-problem kernel)
- *   3: as 0 with 64-byte k-stages        4: as 0 with 4 waves (128x128 per wave)
- *   5: 256x128 tile, 4 waves              6: 128x128 tile, 4 waves, direct global->LDS copies
- *   11: INT8 and bf16 only, rows of whole 128-byte stages only (FQ_ERR_SHAPE otherwise): 256x256 tile, 4 waves
- *      with 128x128 wave tiles (one wave per SIMD), two stage buffers, LDS reads and copies dealt out per
- *      MFMA slot.  The default for large INT8 and bf16 problems with such rows and a bf16 output without bias
- *      (+2 % on live data against 7); other outputs keep 7.
- * fq_gemm_i4_e3m2 has two kernels of its own, both with 256x256 tiles: variant 0 = 8 waves in the ping-pong
- * schedule (wave tile 128x64); any other value = 4 waves with 128x128 wave tiles, LDS reads interleaved
- * between the MFMAs (the default).
+ * fq_gemm_select — tuning and test hook: force the kernel variant that fq_gemm_i8 / fq_gemm_i4 / fq_gemm_bf16 /
+ * fq_bmm_* / fq_linear use ON THE CALLING THREAD (thread-local; other threads keep their own choice, so the
+ * GEMM entry points stay re-entrant).  -1 (default) = chosen from the shape.
+ *   7:  256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the two
+ *       waves of a SIMD alternate LDS-read and MFMA phases, two MFMA k-steps per phase.  One workgroup per
+ *       CU walks its tiles and fetches the first stage of the next tile before it stores the current one.
+ *   10: as 7 with phases twice as long (four MFMA k-steps per phase); the choice for large INT4 problems.
+ *   11: INT8 and bf16 only, rows of whole 128-byte stages only (FQ_ERR_SHAPE otherwise, before anything is
+ *       enqueued): 256x256 tile, 4 waves with 128x128 wave tiles (one wave per SIMD), LDS reads and copies
+ *       dealt out per MFMA slot.  The choice for large INT8 and bf16 problems with such rows and a bf16
+ *       output without bias; other outputs keep 7.
+ *   6:  128x128 tile, 4 waves, direct global->LDS copies (small problems, narrow outputs).
+ *   2:  128x128 tile, 64-byte k-stages, 4 waves, operands staged through registers.
+ * fq_gemm_i4_e3m2 has a single kernel and ignores the hook.
  * Every variant computes the same values.  Returns FQ_ERR_RANGE for an unknown variant.
  * ------------------------------------------------------------------------------------------- */
 int fq_gemm_select(int variant);

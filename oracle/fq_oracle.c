@@ -58,8 +58,8 @@ static int qmin_of(int bits) { return -(1 << (bits - 1)); }
  * increasing j.  Reading taken for the count: total copies n_j = max(1, ceil(max_j / T)),
  * E_j = n_j - 1 (equals Eq. 2's floor except when max_j is an exact multiple of T, where
  * Eq. 2 would add one more, all-zero, channel).  The ratio is evaluated in float64.
- * The final channel count is padded up to a multiple of `align` (Sec. 5.1, "padded to a
- * multiple of 32"); padding slots have src = -1, rep = 0.
+ * The final channel count is rounded up to a multiple of `align` (Sec. 5.1 uses 32); padding
+ * slots have src = -1, rep = 0.
  *
  * Call with cap = 0 (src, rep may be NULL) to obtain Kprime/Kpad only.
  * ---------------------------------------------------------------------------------------- */

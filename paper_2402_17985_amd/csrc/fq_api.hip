@@ -2,7 +2,8 @@
 // of the kernels into the calls declared in include/fq.h.  Nothing here allocates or synchronizes.
 #include <algorithm>
 #include <cmath>
-#include <vector>
+#include <memory>
+#include <new>
 #include <cstdarg>
 #include <cstdio>
 
@@ -59,7 +60,7 @@ int check_map(const int32_t* src_idx, int Kpad, int bits)
     return FQ_OK;
 }
 
-int check_gemm(const void* Xq, const void* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w,
+int check_gemm(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits, const float* s_x, const float* s_w,
                const void* Y, int y_dtype, int ldy)
 {
     if (!Xq || !Wq || !Y) return fail(FQ_ERR_NULL, "Xq, Wq or Y is NULL");
@@ -71,7 +72,11 @@ int check_gemm(const void* Xq, const void* Wq, int M, int N, int Kpad, const flo
     if (Kpad >= 131072) return fail(FQ_ERR_RANGE, "Kpad = %d: int32 accumulators could overflow (needs Kpad < 131072)", Kpad);
     if (ldy < N) return fail(FQ_ERR_SHAPE, "ldy = %d < N = %d", ldy, N);
     if (!aligned16(Xq) || !aligned16(Wq)) return fail(FQ_ERR_ALIGN, "Xq or Wq is not 16-byte aligned");
-    return FQ_OK;
+    // the GEMM kernels address an operand with 32-bit byte offsets
+    const unsigned long long rowbytes = quantized_row_bytes(Kpad, bits);
+    if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
+        return fail(FQ_ERR_RANGE, "a quantized operand of 4 GiB or more (M or N times %llu bytes per row)", rowbytes);
+    return check_forced_variant(bits, (int)rowbytes);
 }
 
 }  // namespace
@@ -106,6 +111,7 @@ int fq_flatten_plan(const float* chmax_host, int K, float T, int align, int32_t*
         if (!(c >= 0.0f) || std::isinf(c))
             return fail(FQ_ERR_RANGE, "chmax[%d] = %g must be finite and >= 0", j, (double)c);
         const double n = std::ceil((double)c / Td);
+        if (n > 1.0e9) return fail(FQ_ERR_RANGE, "chmax[%d] / T = %g: more than 10^9 copies of one channel", j, n);
         if (n > 1.0) extra += (long long)n - 1;
         if (extra > (1LL << 30)) return fail(FQ_ERR_RANGE, "flattened width exceeds 2^30 channels");
     }
@@ -188,10 +194,14 @@ int fq_threshold_boxplot(const float* chmax_host, int K, float beta, float* T_ou
     if (!chmax_host || !T_out_host) return fail(FQ_ERR_NULL, "chmax or T_out is NULL");
     if (K <= 0) return fail(FQ_ERR_SHAPE, "K = %d", K);
     if (!(beta > 0.0f) || std::isinf(beta)) return fail(FQ_ERR_RANGE, "beta = %g must be positive and finite", (double)beta);
-    std::vector<double> v(chmax_host, chmax_host + K);
-    for (int j = 0; j < K; ++j)
+    // sorted copy of the maxima; the allocation must not throw across the C boundary
+    std::unique_ptr<double[]> v(new (std::nothrow) double[(size_t)K]);
+    if (!v) return fail(FQ_ERR_NOMEM, "out of host memory for %d channel maxima", K);
+    for (int j = 0; j < K; ++j) {
+        v[j] = (double)chmax_host[j];
         if (!(v[j] >= 0.0) || std::isinf(v[j])) return fail(FQ_ERR_RANGE, "chmax[%d] = %g must be finite and >= 0", j, v[j]);
-    std::sort(v.begin(), v.end());
+    }
+    std::sort(v.get(), v.get() + K);
     // quartiles by linear interpolation at position q * (K - 1)
     auto quartile = [&](double q) {
         const double pos = q * (double)(K - 1);
@@ -341,7 +351,7 @@ int gemm_common(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits
                 const float* bias, void* Y, int y_dtype, int ldy, void* stream)
 {
     clear_error();
-    int rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
+    int rc = check_gemm(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy);
     if (rc) return rc;
     rc = check_bias(bias, y_dtype);
     if (rc) return rc;
@@ -389,7 +399,7 @@ int bmm_common(const void* Aq, const void* Bq, int batch, int M, int N, int Kpad
                void* stream)
 {
     clear_error();
-    if (int rc = check_gemm(Aq, Bq, M, N, Kpad, s_a, s_b, Y, y_dtype, ldy)) return rc;
+    if (int rc = check_gemm(Aq, Bq, M, N, Kpad, bits, s_a, s_b, Y, y_dtype, ldy)) return rc;
     if (batch < 1 || batch > 65535) return fail(FQ_ERR_RANGE, "batch = %d must lie in [1, 65535]", batch);
     const long long rowbytes = (long long)quantized_row_bytes(Kpad, bits);
     if (stride_a < (long long)M * rowbytes || stride_b < (long long)N * rowbytes)
@@ -444,7 +454,7 @@ int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx, const int3
     void* Xq = base;
     ActWorkspace ws = carve_act_workspace(base + xq_bytes, K, Kpad);
     float* s_x = ws.scalars + 1;
-    rc = check_gemm(Xq, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy);
+    rc = check_gemm(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy);
     if (rc) return rc;
     rc = check_bias(bias, y_dtype);
     if (rc) return rc;

@@ -36,8 +36,9 @@
 //   gemm_wide_kernel  INT8 and bf16: four waves with 128 x 128 wave tiles, reads and copies dealt out
 //                     per MFMA slot (default for large bf16 problems).
 //   gemm_reg_kernel   global -> registers -> LDS, 128x128 tile; a selectable variant.
-// 6-bit pipe: gemm_f6_wide_kernel (four waves, the default) and gemm_f6_kernel (ping-pong).
+// 6-bit pipe: gemm_f6_wide_kernel (four waves with 128 x 128 wave tiles).
 // This file is compiled once per operand mode (see the end of the file).
+#include <atomic>
 #include <type_traits>
 
 #include "fq_internal.h"
@@ -119,6 +120,15 @@ template <> struct OutVec<FQ_F32> { typedef float type __attribute__((ext_vector
 template <> struct OutVec<FQ_F16> { typedef _Float16 type __attribute__((ext_vector_type(4))); };
 template <> struct OutVec<FQ_BF16> { typedef __bf16 type __attribute__((ext_vector_type(4))); };
 
+// fp32 -> half of a value that has already been rounded to fp32.  The empty asm keeps the compiler from folding
+// the preceding fp32 multiply (or bias add) into a mixed-precision instruction that rounds the exact product only
+// once, straight to half: the interface defines the output as the fp32 result rounded again to the output type.
+__device__ __forceinline__ _Float16 half_of_rounded_fp32(float f)
+{
+    asm("" : "+v"(f));
+    return (_Float16)f;
+}
+
 // One output element: the accumulator scaled by s_x * s_w, plus (optionally) the column's bias, both
 // in fp32 as two separately rounded operations, then rounded to the output type.
 template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typename Acc<MODE>::type const& acc, int r, float scale,
@@ -135,7 +145,7 @@ template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typenam
             if (has_bias) f += b;
             if constexpr (YDT == FQ_F32) return f;
             else if constexpr (YDT == FQ_BF16) return (__bf16)f;
-            else return (_Float16)f;
+            else return half_of_rounded_fp32(f);
         }
     } else {
         int v = acc[r];
@@ -147,7 +157,7 @@ template <int MODE, int YDT> __device__ __forceinline__ auto convert_out(typenam
             if (has_bias) f += b;
             if constexpr (YDT == FQ_F32) return f;
             else if constexpr (YDT == FQ_BF16) return (__bf16)f;
-            else return (_Float16)f;
+            else return half_of_rounded_fp32(f);
         }
     }
 }
@@ -667,39 +677,13 @@ __device__ __forceinline__ void gemm_dma_tile(uint8_t* smem, int m0, int n0, con
             set_offsets(m0_next, n0_next);
             issue_any(0);
         }
-    } else if constexpr (PIPE == 0) {
-        // ---- end-of-stage barrier, NSTAGE buffers: NSTAGE-1 stages in flight ----
-#pragma unroll
-        for (int st = 0; st < NSTAGE - 1; ++st)
-            if (st < nk) issue_any(st);
-        if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-        else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-        __syncthreads();
-
-        int buf = 0;
-        for (int kt = 0; kt < nk; ++kt) {
-            const uint8_t* s = smem + buf * STAGE;
-            buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
-            // the buffer refilled here was multiplied in iteration kt-1; every wave has passed that barrier
-            const bool steady = kt + NSTAGE - 1 < nk;
-            if (steady) issue_any(kt + NSTAGE - 1);
-#pragma unroll
-            for (int r = 0; r < NR; ++r) read_frag(s, 0, 0, r);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) slice(ks & 1, s, ks + 1, ks + 1 < KS);
-            // this wave's DMA for stage kt+1 has landed (later stages may still be in flight)
-            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-            __syncthreads();
-        }
     } else {
         // ---- two buffers, barrier before the LAST k-slice of a stage.  By then every wave holds the
         //      operands of that slice in registers, so the stage's buffer is free: the barrier both
         //      publishes stage kt+1 (each wave waited for its own DMA) and releases buffer kt for the
         //      DMA of stage kt+2, and the MFMAs of the last slice overlap the first LDS reads of
         //      stage kt+1, so no wave idles behind the barrier waiting for operands. ----
-        static_assert(PIPE == 0 || (NSTAGE == 2 && KS % 2 == 0), "mid-stage barrier pipeline needs 2 buffers, even KS");
+        static_assert(NSTAGE == 2 && KS % 2 == 0, "mid-stage barrier pipeline needs 2 buffers, even KS");
         issue_any(0);
         __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
         __syncthreads();
@@ -977,7 +961,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
 
 #if FQ_GEMM_MODE == 3
 // =============================================================================================
-// gemm_f6_kernel: 4-bit operands stored as 6-bit E3M2 codes, multiplied on the 6-bit matrix pipe
+// gemm_f6_wide_kernel: 4-bit operands stored as 6-bit E3M2 codes, multiplied on the 6-bit matrix pipe
 // =============================================================================================
 // v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in the E3M2 format runs at twice the INT8 rate.
 // E3M2 represents every integer in [-8, 8] exactly, products are integers of magnitude <= 64 and
@@ -1002,154 +986,9 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
 // this family, this pair of rules is one of those for which a probe kernel measured both reads at full
 // rate (4 cycles per 16-byte, 2.5 per 8-byte wave-read).
 //
-// gemm_f6_tile: tile 256 x 256, 8 waves (2 x 4), wave tile 128 x 64, the ping-pong schedule of
-// gemm_dma_tile with one phase per stage.  A stage is one block (two k-slices), 48 KiB in LDS, three
-// stages in a ring (the stage time is half the INT8 kernel's, so two stages are kept in flight).
-template <int BM, int BN>
-__device__ __forceinline__ void gemm_f6_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
-                                             const uint8_t* __restrict__ B, int M, int N, int rowbytes,
-                                             const float* __restrict__ s_x, const float* __restrict__ s_w,
-                                             void* __restrict__ Y, int y_dtype, int ldy,
-                                             const float* __restrict__ bias)
-{
-    constexpr int WM = 2, WN = 4, NW = 8, NSTAGE = 3;
-    constexpr int SB = 96;                          // stage bytes per row
-    constexpr int CPR = SB / 16;                    // 6 chunks per row
-    constexpr int STAGE = (BM + BN) * SB;
-    constexpr int A_BLOCKS = BM * CPR / 64 / NW;    // 1 KiB copy blocks per wave per stage
-    constexpr int B_BLOCKS = BN * CPR / 64 / NW;
-    constexpr int LPS = A_BLOCKS + B_BLOCKS;
-    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
-    constexpr int KS = 2;                           // 64-deep k-slices per stage
-    constexpr int VM_KEEP = (NSTAGE - 2) * LPS;
-    constexpr int WAIT_KEEP = (VM_KEEP & 0xf) | ((VM_KEEP >> 4) << 14) | 0x0f70;
-    constexpr int WAIT_ALL = 0x0f70;
-    static_assert((BM * CPR) % (64 * NW) == 0 && (BN * CPR) % (64 * NW) == 0, "copy blocks must tile the stage");
-    static_assert(VM_KEEP < 64, "stage count");
-    typedef v16f acc_t;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int nk = rowbytes / SB;                   // whole blocks only (Kpad is a multiple of 128)
-    const size_t blockA = (size_t)M * SB, blockB = (size_t)N * SB;
-
-    // ---- copy mapping: block b of an operand covers LDS chunks 64 b .. 64 b + 63 of its part of the
-    //      stage; chunk c sits in row c / 6 at position c % 6 and holds the global chunk of the same
-    //      row with the two 3-chunk groups swapped when bit 2 ^ bit 3 of the row is set ----
-    uint32_t offA[A_BLOCKS], offB[B_BLOCKS];
-#pragma unroll
-    for (int j = 0; j < A_BLOCKS; ++j) {
-        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
-        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
-        offA[j] = (uint32_t)min(m0 + row, M - 1) * (uint32_t)SB + gc * 16;
-    }
-#pragma unroll
-    for (int j = 0; j < B_BLOCKS; ++j) {
-        const int c = 64 * (wave + j * NW) + lane, row = c / CPR, pos = c % CPR;
-        const int gc = (((row >> 2) ^ (row >> 3)) & 1) ? (pos + 3) % CPR : pos;
-        offB[j] = (uint32_t)min(n0 + row, N - 1) * (uint32_t)SB + gc * 16;
-    }
-    static_assert(A_BLOCKS == B_BLOCKS, "square tile");
-    const uint32_t lds0 = (uint32_t)(size_t)FQ_LDS_PTR(smem) + wave * 1024;
-    auto issue_any = [&](int stage_index) {
-        const uint32_t sA = lds0 + (stage_index % NSTAGE) * STAGE;
-        const uint32_t sB = sA + BM * SB;
-        const uint8_t* gA = A + stage_index * blockA;
-        const uint8_t* gB = B + stage_index * blockB;
-#pragma unroll
-        for (int j = 0; j < A_BLOCKS; ++j) dma16(gA, offA[j], sA + j * NW * 1024);
-#pragma unroll
-        for (int j = 0; j < B_BLOCKS; ++j) dma16(gB, offB[j], sB + j * NW * 1024);
-    };
-
-    // ---- operand read offsets.  A 48-byte group is stored X_a Y_a Y_b X_b (X: first 16, Y: last 8 bytes of
-    //      a 32-code unit's stream) with (a, b) = (0, 1) in rows with bit 4 clear, (1, 0) otherwise: the lane
-    //      of k-half h takes X at 0 / Y at 16 or X at 32 / Y at 24, both reads naturally aligned, and the 8-byte
-    //      reads of 32 consecutive rows fall into four different quarter-positions of the bank cycle ----
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int swp = ((frow >> 2) ^ (frow >> 3)) & 1;
-    const int mirrored = (fhalf ^ (frow >> 4)) & 1;
-    const int a_rd = (wm * TM + frow) * SB, b_rd = BM * SB + (wn * TN + frow) * SB;
-    int xofs[KS], yofs[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        xofs[ks] = 48 * (ks ^ swp) + (mirrored ? 32 : 0);
-        yofs[ks] = 48 * (ks ^ swp) + (mirrored ? 24 : 16);
-    }
-    auto read24 = [&](const uint8_t* p, int ks) -> v8i {
-        const v4i x = *reinterpret_cast<const v4i*>(p + xofs[ks]);
-        const v2i y = *reinterpret_cast<const v2i*>(p + yofs[ks]);
-        return v8i{x[0], x[1], x[2], x[3], y[0], y[1], 0, 0};
-    };
-
-    acc_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    // ---- ping-pong over the stages: see gemm_dma_tile for the barrier bookkeeping (NPH = 1) ----
-    const bool group_b = wave >= 4;
-    v8i pa[KS][FM], pb[KS][FN];
-#pragma unroll
-    for (int st = 0; st < NSTAGE - 1; ++st)
-        if (st < nk) issue_any(st);
-    if (nk >= NSTAGE - 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-    __builtin_amdgcn_s_barrier();
-    if (group_b) __builtin_amdgcn_s_barrier();
-    int buf = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t* s = smem + buf * STAGE;
-        buf = (buf + 1 == NSTAGE) ? 0 : buf + 1;
-        const bool steady = kt + NSTAGE - 1 < nk;
-        // ---------------- memory phase ----------------
-        if (steady) issue_any(kt + NSTAGE - 1);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-            for (int i = 0; i < FM; ++i) pa[ks][i] = read24(s + a_rd + i * 32 * SB, ks);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) pb[ks][j] = read24(s + b_rd + j * 32 * SB, ks);
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);                                 // lgkmcnt(0)
-        if (group_b) {                                                      // B: my copy of stage kt+1 landed
-            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        // ---------------- compute phase ----------------
-        __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pb[ks][j], pa[ks][i], acc[i][j], 3, 3, 0, 127, 0, 127);
-        __builtin_amdgcn_s_setprio(0);
-        if (!group_b) {                                                     // A: my copy of stage kt+1 landed
-            if (steady) __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
-            else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (!group_b) __builtin_amdgcn_s_barrier();
-
-    store_tile<MODE_F6, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy,
-                                smem + wave * (TM * TN * 2), bias);
-}
-
-// The same product with four waves (2 x 2) and wave tiles of 128 x 128: every operand fetched from LDS
-// feeds four MFMAs instead of two or four, which takes the LDS reads from 3/4 to 1/2 of an operand per
-// MFMA -- the ping-pong kernel above is bound by them.  One wave per SIMD: the LDS reads of the next
+// Four waves (2 x 2) with wave tiles of 128 x 128: every operand fetched from LDS feeds four MFMAs, i.e. 1/2
+// of an operand per MFMA (an eight-wave ping-pong schedule with 128 x 64 wave tiles needs 3/4, was bound by
+// those reads at this pipe's rate and measured 25 % slower).  One wave per SIMD: the LDS reads of the next
 // k-slice and their selects are issued between the MFMAs of the current one (operands double-buffered
 // in registers).  Three stage buffers; the barrier sits in the middle of a stage, after the reads of
 // its second slice: it publishes stage kt+1 (each wave waited for its own copies), frees stage kt's
@@ -1215,9 +1054,12 @@ __device__ __forceinline__ void gemm_f6_wide_tile(uint8_t* smem, int m0, int n0,
         else dma16(B + stage_index * blockB, offB[idx - A_BLOCKS], sA + BM * SB + (idx - A_BLOCKS) * NW * 1024);
     };
 
+    // operand read offsets.  A 48-byte group is stored X_a Y_a Y_b X_b (X: first 16, Y: last 8 bytes of a 32-code
+    // unit's stream) with (a, b) = (0, 1) in rows with bit 4 clear, (1, 0) otherwise: the lane of k-half h takes
+    // X at 0 / Y at 16 or X at 32 / Y at 24, both reads naturally aligned
     const int frow = lane & 31, fhalf = lane >> 5;
     const int swp = ((frow >> 2) ^ (frow >> 3)) & 1;
-    const int mirrored = (fhalf ^ (frow >> 4)) & 1;      // see gemm_f6_tile
+    const int mirrored = (fhalf ^ (frow >> 4)) & 1;      // the lane's unit is the second one stored in its group
     const int a_rd = (wm * TM + frow) * SB, b_rd = BM * SB + (wn * TN + frow) * SB;
     int xofs[2], yofs[2];
 #pragma unroll
@@ -1352,20 +1194,6 @@ __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __rest
     }
 }
 
-__global__ __launch_bounds__(512) void gemm_f6_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, int M,
-                                                      int N, int rowbytes, const float* __restrict__ s_x,
-                                                      const float* __restrict__ s_w, void* __restrict__ Y, int y_dtype,
-                                                      int ldy, int tiles_m, int tiles_n, Batch bt)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    A += (size_t)blockIdx.y * bt.stride_a;
-    B += (size_t)blockIdx.y * bt.stride_b;
-    Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
-    int tile_m, tile_n;
-    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
-    gemm_f6_tile<256, 256>(smem, tile_m * 256, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt.bias);
-}
-
 #endif  // FQ_GEMM_MODE == 3
 
 // =============================================================================================
@@ -1478,28 +1306,34 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
     store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy, nullptr, bt.bias);
 }
 
-int set_lds_limit(const void* kern, int smem, bool& attr_set)
+// Raises a kernel's dynamic-LDS limit once per device.  `done` holds one bit per device ordinal (mod 64); a race
+// between two threads only repeats the idempotent call.
+int set_lds_limit(const void* kern, int smem, std::atomic<unsigned long long>& done)
 {
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipFuncSetAttribute(%d bytes LDS): %s", smem, hipGetErrorString(e));
-        attr_set = true;
-    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return FQ_OK;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipFuncSetAttribute(%d bytes LDS): %s", smem, hipGetErrorString(e));
+    done.fetch_or(bit, std::memory_order_release);
     return FQ_OK;
 }
 
+// Compute units of the current device (cached per device ordinal).
 int compute_units()
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
+    static std::atomic<int> cus[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    std::atomic<int>& slot = cus[dev & 63];
+    int n = slot.load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        slot.store(n, std::memory_order_relaxed);
     }
-    return cus;
+    return n;
 }
 
 template <int MODE, int BM, int BN, int BKB, int WM, int WN, int NSTAGE, int PIPE, int PP_SLICES = 2, bool ONLY_BF16 = false>
@@ -1511,7 +1345,7 @@ int launch_dma(const void* A, const void* B, int M, int N, int rowbytes, const f
         return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
     auto kern = gemm_dma_kernel<MODE, BM, BN, BKB, WM, WN, NSTAGE, PIPE, PP_SLICES, ONLY_BF16>;
     constexpr int smem = NSTAGE * (BM + BN) * BKB;
-    static bool attr_set = false;
+    static std::atomic<unsigned long long> attr_set{0};
     if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const long long tiles = (long long)tiles_m * tiles_n;
@@ -1544,7 +1378,7 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
 {
     auto kern = gemm_reg_kernel<MODE, BM, BN, BKB, WM, WN>;
     constexpr int smem = 2 * (BM + BN) * BKB;
-    static bool attr_set = false;
+    static std::atomic<unsigned long long> attr_set{0};
     if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set)) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const long long tiles = (long long)tiles_m * tiles_n;
@@ -1569,7 +1403,7 @@ int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const 
         const bool only_bf16 = y_dtype == FQ_BF16 && !bt.bias;
         auto kern = only_bf16 ? gemm_wide_kernel<MODE, true> : gemm_wide_kernel<MODE, false>;
         constexpr int smem = 2 * 512 * 128;
-        static bool attr_set[2] = {false, false};
+        static std::atomic<unsigned long long> attr_set[2];
         if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set[only_bf16 ? 1 : 0])) return rc;
         const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
         const long long tiles = (long long)tiles_m * tiles_n;
@@ -1613,20 +1447,13 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
             v = 11;
     }
     switch (v) {
-    case 0: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 1: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 0>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 2: return launch_reg<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 3: return launch_dma<MODE, 256, 256, 64, 2, 4, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 4: return launch_dma<MODE, 256, 256, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 5: return launch_dma<MODE, 256, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 6: return launch_dma<MODE, 128, 128, 128, 2, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 7:
         // the large-problem kernels have an instantiation with the plain bf16 epilogue only (no spills)
         if (MODE != MODE_BF16 && y_dtype == FQ_BF16 && !bt.bias)
             return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2, true>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
         return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 8: return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 1>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
-    case 9: return launch_dma<MODE, 256, 256, 64, 2, 4, 4, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
     case 10:
         if (MODE != MODE_BF16 && y_dtype == FQ_BF16 && !bt.bias)
             return launch_dma<MODE, 256, 256, 128, 2, 4, 2, 2, 4, true>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
@@ -1652,33 +1479,25 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
         return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
     if (rowbytes % 96) return fail(FQ_ERR_SHAPE, "E3M2 rows must be whole 96-byte blocks");
     constexpr int smem = 3 * 512 * 96;
-    static bool attr_set = false;
-    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_kernel), smem, attr_set)) return rc;
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long tiles = (long long)tiles_m * tiles_n;
     if (tiles > 0x3fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
-    static bool attr_set_wide = false, attr_set_wide_bf16 = false;
-    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel<false>), smem, attr_set_wide)) return rc;
-    if (int rc = set_lds_limit(reinterpret_cast<const void*>(gemm_f6_wide_kernel<true>), smem, attr_set_wide_bf16)) return rc;
-    if (forced_gemm_variant() != 0) {
-        // a last round that would occupy at most half of the CUs is run as half-height tiles instead
-        const int cus = compute_units();
-        const int r = (int)(tiles % cus);
-        int n_main = (int)tiles, n_tail = 0;
-        if (bt.count == 1 && r > 0 && 2 * r <= cus) {
-            n_tail = r;
-            n_main = (int)tiles - r;
-        }
-        // the common case (bf16 output, no bias) has an instantiation with that epilogue only
-        auto kern = (y_dtype == FQ_BF16 && !bt.bias) ? gemm_f6_wide_kernel<true> : gemm_f6_wide_kernel<false>;
-        kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
-            static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
-            tiles_m, tiles_n, n_main, bt);
+    // the common case (bf16 output, no bias) has an instantiation with that epilogue only
+    const bool only_bf16 = y_dtype == FQ_BF16 && !bt.bias;
+    auto kern = only_bf16 ? gemm_f6_wide_kernel<true> : gemm_f6_wide_kernel<false>;
+    static std::atomic<unsigned long long> attr_set[2];
+    if (int rc = set_lds_limit(reinterpret_cast<const void*>(kern), smem, attr_set[only_bf16 ? 1 : 0])) return rc;
+    // a last round that would occupy at most half of the CUs is run as half-height tiles instead
+    const int cus = compute_units();
+    const int r = (int)(tiles % cus);
+    int n_main = (int)tiles, n_tail = 0;
+    if (bt.count == 1 && r > 0 && 2 * r <= cus) {
+        n_tail = r;
+        n_main = (int)tiles - r;
     }
-    else
-        gemm_f6_kernel<<<dim3((unsigned)tiles, (unsigned)bt.count), dim3(512), smem, stream>>>(
-            static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
-            tiles_m, tiles_n, bt);
+    kern<<<dim3((unsigned)(n_main + 2 * n_tail), (unsigned)bt.count), dim3(256), smem, stream>>>(
+        static_cast<const uint8_t*>(A), static_cast<const uint8_t*>(B), M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy,
+        tiles_m, tiles_n, n_main, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
     return FQ_OK;

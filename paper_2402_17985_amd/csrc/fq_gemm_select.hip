@@ -5,17 +5,28 @@
 namespace fq {
 
 namespace {
-constexpr int NUM_VARIANTS = 12;
-// Forced kernel variant (-1 = automatic); a tuning hook, see fq_gemm_select().
-int g_variant = -1;
+// Forced kernel variant of the calling thread (-1 = automatic); a tuning and test hook, see fq_gemm_select().
+// Thread-local, so concurrent callers of the GEMM entry points never see each other's choice.
+thread_local int g_variant = -1;
 }  // namespace
 
 int forced_gemm_variant() { return g_variant; }
 
 int set_gemm_variant(int v)
 {
-    if (v < -1 || v >= NUM_VARIANTS) return fail(FQ_ERR_RANGE, "unknown GEMM variant %d", v);
+    if (v != -1 && v != 2 && v != 6 && v != 7 && v != 10 && v != 11)
+        return fail(FQ_ERR_RANGE, "unknown GEMM variant %d (valid: -1, 2, 6, 7, 10, 11)", v);
     g_variant = v;
+    return FQ_OK;
+}
+
+// What a forced variant cannot run, checked before anything is enqueued (rowbytes = bytes of a quantized row).
+int check_forced_variant(int bits, int rowbytes)
+{
+    if (g_variant != 11) return FQ_OK;
+    if (bits == FQ_BITS_I4_E3M2) return FQ_OK;              // the 6-bit GEMM has one kernel and ignores the hook
+    if (bits != 8) return fail(FQ_ERR_RANGE, "GEMM variant 11 exists for INT8 and bf16 operands only");
+    if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variant 11 needs rows of whole 128-byte stages");
     return FQ_OK;
 }
 

@@ -68,6 +68,7 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
                        void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream);
 int forced_gemm_variant();   // -1 = choose from the shape
 int set_gemm_variant(int v);
+int check_forced_variant(int bits, int rowbytes);   // FQ_OK unless the forced variant cannot run this operand
 
 // bias: optional fp32 [N] (16-byte aligned) added after scaling; must be null for FQ_I32 output
 int launch_gemm_int(const void* Xq, const void* Wq, int M, int N, int Kpad, int bits,

@@ -18,6 +18,8 @@
 //   flatten_quant       the general form (one thread per 16 slots and strip of rows, every slot
 //                       gathered from global memory): the peel split of Eq. 3 as printed, and layers
 //                       too wide for the row-strip kernel's LDS budget
+#include <atomic>
+
 #include "fq_internal.h"
 
 namespace fq {
@@ -716,6 +718,18 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
         if (peel || K < 16 || kq1 + tail1 > 64u * 1024u)
             return fail(FQ_ERR_DTYPE, "E3M2 storage (bits = 6) needs K >= 16 and a layer narrow enough for the "
                                       "row-strip kernel, and is not available for the peel split");
+        // very wide layers launch this kernel with up to 128 KiB of LDS: raise its limit once per device
+        static std::atomic<unsigned long long> raised{0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (!(raised.load(std::memory_order_acquire) & bit)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(flatten_quant_rows_kernel<DT, 6>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+            if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipFuncSetAttribute(128 KiB LDS): %s", hipGetErrorString(e));
+            raised.fetch_or(bit, std::memory_order_release);
+        }
     }
     if (mode != 1 && mode != 4) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, T,
@@ -747,12 +761,7 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
                     R6 = 2 * R;
                     lds6 = (size_t)R6 * kq + tail_src;
                     nthr6 = 512;
-                    static bool attr = false;
-                    if (!attr) {
-                        hipFuncSetAttribute(reinterpret_cast<const void*>(flatten_quant_rows_kernel<DT, 6>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-                        attr = true;
-                    }
+                    // (the kernel's LDS limit was raised above, before anything of this call was enqueued)
                 }
                 flatten_quant_rows_kernel<DT, 6><<<(unsigned)((M + R6 - 1) / R6), nthr6, lds6, stream>>>(X, M, K, ld, src_idx, ws.mslot, ws.gflag, Kpad, R6, o8);
             }

@@ -121,6 +121,7 @@ def test_device_calls_validate_before_launching():
     assert L.fq_channel_absmax(dummy, fq.FQ_BF16, 4, 64, 60, 0, dummy, None) == 2
     assert L.fq_channel_absmax(dummy, fq.FQ_BF16, 4, 64, 64, 0, None, None) == 1
     assert L.fq_gemm_select(1700) == 4
+    assert L.fq_gemm_select(0) == 4                          # a variant that no longer exists
     assert L.fq_gemm_select(-1) == 0
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 8) >= 8 * 64 + ws
     assert fq.fq_linear_workspace_bytes(8, 64, 64, 4) >= 8 * 32 + ws

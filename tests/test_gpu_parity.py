@@ -207,7 +207,7 @@ def _gemm_acc(Xq, Wq, bits):
     return Y.cpu().numpy()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [2, 6, 7, 10])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_gemm_accumulators_bit_exact(variant, bits):
     rng = np.random.default_rng(100 * variant + bits)
@@ -302,7 +302,7 @@ def test_linear_is_deterministic():
 # ------------------------------------------------------------------------------------------
 # bf16 baseline GEMM
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant,K", [(0, 1032), (2, 1032), (11, 1024), (11, 192)])
+@pytest.mark.parametrize("variant,K", [(7, 1032), (2, 1032), (11, 1024), (11, 192)])
 def test_gemm_bf16_baseline(variant, K):
     rng = np.random.default_rng(9)
     M, N = 300, 260
@@ -412,7 +412,7 @@ def test_bmm_accumulators_bit_exact(batch, M, N, Kpad, bits):
     np.testing.assert_array_equal(Y.cpu().numpy(), ref)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 5, 6, 7, 10])
+@pytest.mark.parametrize("variant", [2, 6, 7, 10])
 def test_bmm_variants_and_padded_strides(variant):
     """Every kernel family with batch strides larger than one matrix (operands and output live in
     wider buffers; the gaps must stay untouched) and a 2-byte dequantized output."""
