@@ -166,6 +166,27 @@ int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx,
 size_t fq_act_workspace_bytes(int K, int Kpad);
 
 /* ---------------------------------------------------------------------------------------------
+ * fq_flatten_quant_act_noalloc — fq_flatten_quant_act for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is
+ * a fixed array of FQ_NOALLOC_SCRATCH_BYTES that is part of the library's device image (one copy on every
+ * GPU that loads the library, held until the process ends), so the caller passes inputs and outputs only.
+ * The call allocates and frees nothing, and computes exactly what fq_flatten_quant_act computes (same
+ * kernels, same bytes).
+ *
+ * Limit: fq_act_workspace_bytes(K, Kpad) <= FQ_NOALLOC_SCRATCH_BYTES (e.g. K = 32768 with Kpad = 65536),
+ * else FQ_ERR_WORKSPACE and nothing is enqueued.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress; FQ_ERR_HIP if that fails).
+ * All calls on one GPU share that GPU's array and it keeps the previous call's contents; what has to start
+ * at zero is cleared by a kernel inside every call (no memset node, so the call may be captured).  Calls
+ * that overlap on one GPU (different streams, or threads without ordering) race on the array: order them.
+ * ------------------------------------------------------------------------------------------- */
+#define FQ_NOALLOC_SCRATCH_BYTES (1u << 20)
+int fq_flatten_quant_act_noalloc(const void* X, int x_dtype, int M, int K, int ldx,
+                                 const int32_t* src_idx, const int32_t* rep, int Kpad, int bits,
+                                 const float* absmax_in, void* Xq_out, float* s_x_out, void* stream);
+size_t fq_noalloc_scratch_bytes(void);
+
+/* ---------------------------------------------------------------------------------------------
  * Eq. 3 as printed ("peel" split) and flattening of the weights' own channels (Sec. 4.1, last
  * paragraph).  The map layout, the GEMM and its epilogue are the ones above.
  *

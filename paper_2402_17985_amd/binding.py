@@ -24,7 +24,8 @@ SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
            "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
            "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel",
-           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_gemm_i4_e3m2"]
+           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_gemm_i4_e3m2",
+           "fq_flatten_quant_act_noalloc", "fq_noalloc_scratch_bytes"]
 FQ_BITS_I4_E3M2 = 6   # the 4-bit quantizer with its values stored as 6-bit E3M2 codes
 
 
@@ -66,6 +67,9 @@ def lib() -> ctypes.CDLL:
     L.fq_weights_workspace_bytes.argtypes = [c_int, c_int]
     L.fq_flatten_quant_act.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, vp, vp, vp, vp,
                                        c_size_t, vp]
+    L.fq_flatten_quant_act_noalloc.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, vp, vp, vp, vp]
+    L.fq_noalloc_scratch_bytes.restype = c_size_t
+    L.fq_noalloc_scratch_bytes.argtypes = []
     L.fq_act_workspace_bytes.restype = c_size_t
     L.fq_act_workspace_bytes.argtypes = [c_int, c_int]
     for f in (L.fq_gemm_i8, L.fq_gemm_i4):
@@ -242,6 +246,20 @@ def fq_flatten_quant_act(X, src_idx, rep, bits: int, Xq_out, s_x_out, workspace,
                                       rep.data_ptr(), Kpad, bits, _ptr(absmax_in), Xq_out.data_ptr(),
                                       s_x_out.data_ptr(), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fq_noalloc_scratch_bytes() -> int:
+    return int(lib().fq_noalloc_scratch_bytes())
+
+
+def fq_flatten_quant_act_noalloc(X, src_idx, rep, bits: int, Xq_out, s_x_out, absmax_in=None, stream=None) -> None:
+    """fq_flatten_quant_act with the workspace inside the library's device image (nothing is allocated)."""
+    _dev2d(X, "X")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    _check(lib().fq_flatten_quant_act_noalloc(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(),
+                                              rep.data_ptr(), Kpad, bits, _ptr(absmax_in), Xq_out.data_ptr(),
+                                              s_x_out.data_ptr(), _stream(stream)))
 
 
 def _gemm(fn, Xq, Wq, M, N, Kpad, s_x, s_w, Y, stream):

@@ -6,6 +6,7 @@
 #include <new>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "fq_internal.h"
 
@@ -305,6 +306,71 @@ int fq_flatten_quant_act(const void* X, int x_dtype, int M, int K, int ldx, cons
         return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes,
                     fq_act_workspace_bytes(K, Kpad));
     ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
+    return launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in,
+                                Xq_out, s_x_out, ws, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------------
+// fq_flatten_quant_act_noalloc: the workspace of fq_flatten_quant_act held in device memory that belongs
+// to the library's code object, for callers that cannot allocate.
+// ---------------------------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+constexpr size_t NOALLOC_SCRATCH_BYTES = FQ_NOALLOC_SCRATCH_BYTES;
+// One copy per GPU that loads the library, at that GPU's own address, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(FQ_ERR_RANGE, "device ordinal %d beyond %d", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(FQ_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FQ_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t fq_noalloc_scratch_bytes(void) { return NOALLOC_SCRATCH_BYTES; }
+
+int fq_flatten_quant_act_noalloc(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx,
+                                 const int32_t* rep, int Kpad, int bits, const float* absmax_in, void* Xq_out,
+                                 float* s_x_out, void* stream)
+{
+    clear_error();
+    int rc = check_matrix("X", X, x_dtype, M, K, ldx);
+    if (rc) return rc;
+    rc = check_map(src_idx, Kpad, bits);
+    if (rc) return rc;
+    if (!rep || !Xq_out || !s_x_out) return fail(FQ_ERR_NULL, "rep, Xq_out or s_x_out is NULL");
+    if (!aligned16(Xq_out)) return fail(FQ_ERR_ALIGN, "Xq_out is not 16-byte aligned");
+    const size_t need = fq_act_workspace_bytes(K, Kpad);
+    if (need > NOALLOC_SCRATCH_BYTES)
+        return fail(FQ_ERR_WORKSPACE, "K = %d, Kpad = %d need %zu bytes of scratch, beyond the built-in %zu: use "
+                                      "fq_flatten_quant_act with a caller-owned workspace", K, Kpad, need,
+                    NOALLOC_SCRATCH_BYTES);
+    void* base = nullptr;
+    rc = scratch_of_current_device(&base);
+    if (rc) return rc;
+    // cmax, the part of the scratch that must start at zero, is cleared by a fill kernel inside the launch
+    ActWorkspace ws = carve_act_workspace(base, K, Kpad);
     return launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, bits, absmax_in ? 1 : 0, absmax_in,
                                 Xq_out, s_x_out, ws, static_cast<hipStream_t>(stream));
 }
