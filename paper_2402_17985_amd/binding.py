@@ -25,7 +25,10 @@ SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_
            "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
            "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel",
            "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_gemm_i4_e3m2",
-           "fq_flatten_quant_act_noalloc", "fq_noalloc_scratch_bytes"]
+           "fq_flatten_quant_act_noalloc", "fq_noalloc_scratch_bytes",
+           # include/fq_peak.h: measurement hooks
+           "fq_peak_mfma", "fq_peak_copy", "fq_peak_gemm_ticks", "fq_peak_wall_clock_khz"]
+FQ_PEAK_I8, FQ_PEAK_BF16, FQ_PEAK_E3M2, FQ_PEAK_I8_NIBBLES = 0, 1, 2, 3
 FQ_BITS_I4_E3M2 = 6   # the 4-bit quantizer with its values stored as 6-bit E3M2 codes
 
 
@@ -70,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.fq_flatten_quant_act_noalloc.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, c_int, vp, vp, vp, vp]
     L.fq_noalloc_scratch_bytes.restype = c_size_t
     L.fq_noalloc_scratch_bytes.argtypes = []
+    L.fq_peak_mfma.argtypes = [c_int, vp, c_size_t, c_int, ctypes.c_longlong, vp, vp, vp]
+    L.fq_peak_copy.argtypes = [vp, vp, c_size_t, vp]
+    L.fq_peak_gemm_ticks.argtypes = [vp]
+    L.fq_peak_wall_clock_khz.argtypes = []
     L.fq_act_workspace_bytes.restype = c_size_t
     L.fq_act_workspace_bytes.argtypes = [c_int, c_int]
     for f in (L.fq_gemm_i8, L.fq_gemm_i4):
@@ -260,6 +267,29 @@ def fq_flatten_quant_act_noalloc(X, src_idx, rep, bits: int, Xq_out, s_x_out, ab
     _check(lib().fq_flatten_quant_act_noalloc(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(),
                                               rep.data_ptr(), Kpad, bits, _ptr(absmax_in), Xq_out.data_ptr(),
                                               s_x_out.data_ptr(), _stream(stream)))
+
+
+def fq_peak_mfma(kind: int, operands, blocks: int, iters: int, ticks_out, sink, stream=None) -> None:
+    """MFMA-only issue loop (include/fq_peak.h).  operands: a device tensor of >= 64 KiB, or None for zeros."""
+    nbytes = 0 if operands is None else operands.numel() * operands.element_size()
+    _check(lib().fq_peak_mfma(kind, _ptr(operands), nbytes, blocks, iters, _ptr(ticks_out), sink.data_ptr(),
+                              _stream(stream)))
+
+
+def fq_peak_gemm_ticks(ticks) -> None:
+    """ticks: int64 device tensor [2] the GEMM kernels launched from this thread add their clock ticks to, or None."""
+    _check(lib().fq_peak_gemm_ticks(_ptr(ticks)))
+
+
+def fq_peak_wall_clock_khz() -> int:
+    return int(lib().fq_peak_wall_clock_khz())
+
+
+def fq_peak_copy(src, dst, stream=None) -> None:
+    """Plain device copy of src into dst (same byte size, a multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(lib().fq_peak_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))
 
 
 def _gemm(fn, Xq, Wq, M, N, Kpad, s_x, s_w, Y, stream):

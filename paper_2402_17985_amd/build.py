@@ -13,7 +13,7 @@ SOURCES = [("fq_gemm.hip", ["-DFQ_GEMM_MODE=1"], "fq_gemm_i4.o"),
            ("fq_gemm.hip", ["-DFQ_GEMM_MODE=2"], "fq_gemm_bf16.o"),
            ("fq_gemm.hip", ["-DFQ_GEMM_MODE=3"], "fq_gemm_f6.o"),
            ("fq_api.hip", [], "fq_api.o"), ("fq_quant.hip", [], "fq_quant.o"),
-           ("fq_gemm_select.hip", [], "fq_gemm_select.o")]
+           ("fq_gemm_select.hip", [], "fq_gemm_select.o"), ("fq_peak.hip", [], "fq_peak.o")]
 # -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions
 # -ffp-contract=off: every fp32 multiply stays a single correctly rounded operation
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -36,7 +36,8 @@ def _newer(target, deps):
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    hdrs = [os.path.join(CSRC, "fq_internal.h"), os.path.join(HERE, "..", "include", "fq.h")]
+    hdrs = [os.path.join(CSRC, "fq_internal.h"), os.path.join(HERE, "..", "include", "fq.h"),
+            os.path.join(HERE, "..", "include", "fq_peak.h")]
     srcs = [(os.path.join(CSRC, s), extra, obj) for s, extra, obj in SOURCES]
     if not force and _newer(OUT, [s for s, _, _ in srcs] + hdrs):
         return OUT

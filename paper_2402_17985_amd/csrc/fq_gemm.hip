@@ -82,6 +82,30 @@ __device__ __forceinline__ void dma16_addr(const uint8_t* lane_address, uint32_t
 // 16 zero bytes in device memory: the source of DMA lanes that fall beyond the end of a row.
 __device__ const int g_zero_chunk[4] = {0, 0, 0, 0};
 
+// Clock probe (measurement hook): with a non-null counter pair, the first wave of the workgroup adds the shader-clock
+// and the constant-rate ticks between construction and finish().  Both reads are scalar instructions.
+struct ClockProbe {
+    unsigned long long t0, r0;
+    __device__ __forceinline__ explicit ClockProbe(const unsigned long long* ticks)
+    {
+        t0 = r0 = 0;
+        if (ticks) {
+            t0 = __builtin_amdgcn_s_memtime();
+            r0 = __builtin_amdgcn_s_memrealtime();
+        }
+    }
+    __device__ __forceinline__ void finish(unsigned long long* ticks) const
+    {
+        if (ticks) {
+            const unsigned long long t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+            if (threadIdx.x == 0) {
+                atomicAdd(&ticks[0], t1 - t0);
+                atomicAdd(&ticks[1], r1 - r0);
+            }
+        }
+    }
+};
+
 template <int MODE> struct Acc { typedef v16i type; };
 template <> struct Acc<MODE_BF16> { typedef v16f type; };
 template <> struct Acc<MODE_F6> { typedef v16f type; };      // exact integers below 2^24 held in fp32
@@ -735,6 +759,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
                                                                 int tiles_m, int tiles_n, int n_main, int n_tail, Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    const ClockProbe probe(bt.ticks);
     // batched launches: blockIdx.y selects the problem
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
@@ -769,6 +794,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const uint8_t* __
         // (a tile that was prefetched synchronizes on its own first barrier instead, after its waits)
         if (v + (int)gridDim.x < n_ids && !prefetched) __syncthreads();
     }
+    probe.finish(bt.ticks);
 }
 
 // =============================================================================================
@@ -942,6 +968,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
                                                         int ldy, int tiles_m, int tiles_n, int n_main, Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    const ClockProbe probe(bt.ticks);
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
     Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
@@ -957,6 +984,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
         gemm_wide_tile<MODE, 128, 256, ONLY_BF16>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w,
                                        Y, y_dtype, ldy, bt.bias);
     }
+    probe.finish(bt.ticks);
 }
 
 #if FQ_GEMM_MODE == 3
@@ -1177,6 +1205,7 @@ __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __rest
                                                            Batch bt)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    const ClockProbe probe(bt.ticks);
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
     Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
@@ -1192,6 +1221,7 @@ __global__ __launch_bounds__(256) void gemm_f6_wide_kernel(const uint8_t* __rest
         gemm_f6_wide_tile<128, 256, ONLY_BF16>(smem, tile_m * 256 + (t & 1) * 128, tile_n * 256, A, B, M, N, rowbytes, s_x, s_w, Y,
                                     y_dtype, ldy, bt.bias);
     }
+    probe.finish(bt.ticks);
 }
 
 #endif  // FQ_GEMM_MODE == 3
@@ -1207,6 +1237,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
                                                                 void* __restrict__ Y, int y_dtype, int ldy,
                                                                 int tiles_m, int tiles_n, Batch bt)
 {
+    const ClockProbe probe(bt.ticks);
     A += (size_t)blockIdx.y * bt.stride_a;
     B += (size_t)blockIdx.y * bt.stride_b;
     Y = static_cast<uint8_t*>(Y) + (size_t)blockIdx.y * bt.stride_y;
@@ -1304,6 +1335,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_reg_kernel(const uint8_t* __
     }
 
     store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, s_x, s_w, Y, y_dtype, ldy, nullptr, bt.bias);
+    probe.finish(bt.ticks);
 }
 
 // Raises a kernel's dynamic-LDS limit once per device.  `done` holds one bit per device ordinal (mod 64); a race

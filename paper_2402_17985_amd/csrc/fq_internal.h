@@ -55,7 +55,11 @@ struct Batch {
     int count;
     size_t stride_a, stride_b, stride_y;
     const float* bias;   // optional fp32 [N] added to the scaled accumulators (shared by the batch), or null
+    unsigned long long* ticks;   // measurement hook (fq_peak_gemm_ticks): null, or two counters every workgroup adds
+                                 // the shader-clock and constant-rate ticks of its first wave to
 };
+unsigned long long* gemm_ticks_pointer();   // the calling thread's hook value
+void g_ticks_set(unsigned long long* p);
 
 // Per-mode dispatchers (one translation unit each): A [M, rowbytes], B [N, rowbytes] bytes
 int gemm_dispatch_i8(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
