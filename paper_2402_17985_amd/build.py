@@ -40,7 +40,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             os.path.join(HERE, "..", "include", "fq_peak.h")]
     srcs = [(os.path.join(CSRC, s), extra, obj) for s, extra, obj in SOURCES]
     if not force and _newer(OUT, [s for s, _, _ in srcs] + hdrs):
-        return OUT
+        return OUT                          # nothing changed since the library was linked
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
@@ -48,6 +48,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     def compile_one(item):
         src, extra, objname = item
         obj = os.path.join(objdir, objname)
+        if not force and _newer(obj, [src] + hdrs):
+            return obj                      # incremental build: this object is up to date
         cmd = [hipcc] + FLAGS + extra + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -66,5 +68,6 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    # `python -m paper_2402_17985_amd.build` rebuilds everything; `... build --changed` only what changed
+    print(build(force="--changed" not in sys.argv, verbose=True))
     sys.exit(0)

@@ -20,8 +20,8 @@ int forced_gemm_variant() { return g_variant; }
 
 int set_gemm_variant(int v)
 {
-    if (v != -1 && v != 2 && v != 6 && v != 7 && v != 10 && v != 11)
-        return fail(FQ_ERR_RANGE, "unknown GEMM variant %d (valid: -1, 2, 6, 7, 10, 11)", v);
+    if (v != -1 && v != 2 && v != 6 && v != 7 && v != 10 && v != 11 && v != 12)
+        return fail(FQ_ERR_RANGE, "unknown GEMM variant %d (valid: -1, 2, 6, 7, 10, 11, 12)", v);
     g_variant = v;
     return FQ_OK;
 }
@@ -29,10 +29,10 @@ int set_gemm_variant(int v)
 // What a forced variant cannot run, checked before anything is enqueued (rowbytes = bytes of a quantized row).
 int check_forced_variant(int bits, int rowbytes)
 {
-    if (g_variant != 11) return FQ_OK;
+    if (g_variant != 11 && g_variant != 12) return FQ_OK;
     if (bits == FQ_BITS_I4_E3M2) return FQ_OK;              // the 6-bit GEMM has one kernel and ignores the hook
-    if (bits != 8) return fail(FQ_ERR_RANGE, "GEMM variant 11 exists for INT8 and bf16 operands only");
-    if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variant 11 needs rows of whole 128-byte stages");
+    if (bits != 8) return fail(FQ_ERR_RANGE, "GEMM variants 11 and 12 exist for INT8 and bf16 operands only");
+    if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variants 11 and 12 need rows of whole 128-byte stages");
     return FQ_OK;
 }
 

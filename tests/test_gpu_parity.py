@@ -302,7 +302,7 @@ def test_linear_is_deterministic():
 # ------------------------------------------------------------------------------------------
 # bf16 baseline GEMM
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant,K", [(7, 1032), (2, 1032), (11, 1024), (11, 192)])
+@pytest.mark.parametrize("variant,K", [(7, 1032), (2, 1032), (11, 1024), (11, 192), (12, 1024), (12, 192), (12, 64), (12, 128)])
 def test_gemm_bf16_baseline(variant, K):
     rng = np.random.default_rng(9)
     M, N = 300, 260
@@ -671,11 +671,12 @@ def test_gemm_more_tiles_than_compute_units(bits):
 # ------------------------------------------------------------------------------------------
 # the four-wave kernel with 128 x 128 wave tiles (INT8 and bf16 only)
 # ------------------------------------------------------------------------------------------
-def test_gemm_four_wave_kernel_int8():
-    """Variant 11: raw accumulators on ragged shapes (masked last k-stage, one-stage and two-stage reductions),
+@pytest.mark.parametrize("variant", [11, 12])
+def test_gemm_four_wave_kernel_int8(variant):
+    """Variants 11 and 12 (two stage buffers / A three deep and B two deep, copies staggered over the waves): raw accumulators on ragged shapes (masked last k-stage, one-stage and two-stage reductions),
     a grid with half-height tail tiles, the staged 2-byte epilogue with bias, and a batched launch."""
     rng = np.random.default_rng(1100)
-    fq.fq_gemm_select(11)
+    fq.fq_gemm_select(variant)
     try:
         for (M, N, Kpad) in [(300, 520, 384), (257, 129, 1152), (1, 1, 128), (33, 700, 256), (512, 256, 128), (70, 41, 640),
                              (17 * 256 - 20, 16 * 256 - 7, 256)]:
@@ -711,8 +712,9 @@ def test_gemm_four_wave_kernel_int8():
         fq.fq_gemm_select(-1)
 
 
-def test_gemm_four_wave_kernel_rejects_nibbles_and_partial_stages():
-    fq.fq_gemm_select(11)
+@pytest.mark.parametrize("variant", [11, 12])
+def test_gemm_four_wave_kernel_rejects_nibbles_and_partial_stages(variant):
+    fq.fq_gemm_select(variant)
     try:
         Xq = torch.zeros((4, 16), dtype=torch.uint8, device=DEV)
         Y = torch.zeros((4, 4), dtype=torch.int32, device=DEV)
