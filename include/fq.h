@@ -348,13 +348,14 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *   7:  256x256 tile, 128-byte k-stages, 8 waves, direct global->LDS copies, ping-pong schedule: the two
  *       waves of a SIMD alternate LDS-read and MFMA phases, two MFMA k-steps per phase.  One workgroup per
  *       CU walks its tiles and fetches the first stage of the next tile before it stores the current one.
- *   10: as 7 with phases twice as long (four MFMA k-steps per phase); the choice for large INT4 problems.
+ *   10: as 7 with phases twice as long (four MFMA k-steps per phase); large INT4 problems that 12 cannot run.
  *   11: INT8 and bf16 only, rows of whole 128-byte stages only (FQ_ERR_SHAPE otherwise, before anything is
  *       enqueued): 256x256 tile, 4 waves with 128x128 wave tiles (one wave per SIMD), two stage buffers, LDS
  *       reads and copies dealt out per MFMA slot.
  *   12: as 11 with all of LDS as stage buffers (A three deep, B two deep) so that the global->LDS copies are
- *       spread over the whole stage, one copy instruction of one wave per MFMA slot.  The choice for large INT8
- *       and bf16 problems with such rows and a bf16 output without bias; other outputs keep 7.
+ *       spread over the whole stage, one copy instruction of one wave per MFMA slot; also for packed INT4, whose
+ *       nibble widening is dealt out over the MFMA slots as well.  The choice for large problems with such rows
+ *       and a bf16 output without bias; other outputs keep 7 (INT8, bf16) or 10 (INT4).
  *   6:  128x128 tile, 4 waves, direct global->LDS copies (small problems, narrow outputs).
  *   2:  128x128 tile, 64-byte k-stages, 4 waves, operands staged through registers.
  * fq_gemm_i4_e3m2 has a single kernel and ignores the hook.

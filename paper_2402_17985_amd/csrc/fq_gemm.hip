@@ -1006,7 +1006,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
 }
 
 // =============================================================================================
-// gemm_deep_kernel (INT8, bf16): four waves with 128 x 128 wave tiles, A staged three deep, B two deep
+// gemm_deep_kernel (INT8, packed INT4, bf16): four waves with 128 x 128 wave tiles, A staged three deep, B two deep
 // =============================================================================================
 // What bounds gemm_wide_kernel: a global->LDS copy instruction moves 1 KiB and keeps the address unit of the CU busy
 // for 16 cycles (64 bytes per cycle), so the 64 copies of a 128-byte stage take it 1024 cycles -- half of the stage's
@@ -1023,6 +1023,32 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint8_t* __restric
 //              slice 3   first half of B(kt+2)    (into the B buffer this barrier frees)
 // The wave index is a template parameter (four instantiations of the tile, selected once per workgroup): the stagger
 // costs no branches inside the loop.  Rows must be whole 128-byte stages, as for gemm_wide_kernel.
+// Widening steps of a packed-nibble slice of gemm_deep_tile: the (at most two) steps issued after MFMA slot `sl`
+// (low pass = slots [0, NM), high pass = [NM, 2 NM), NM = 4 FM).  A step is kind * 8 + operand, operand 0..3 = a0..a3,
+// 4..7 = b0..b3.  Low pass: the low halves of a1.. (a0 and every b come in ready), then every high half, in the order
+// the high pass first uses them.  High pass (its slots t = 0.. also issue the LDS reads of the next slice, a0 b0 b1 b2
+// b3 a1.. one per slot): the low halves of the next slice's a0, b0..b3, each at least three slots after its read.
+enum { W_NONE = 0, W_SH = 1, W_AN = 2, W_HI = 3, W_SHN = 4 };
+template <int FM> constexpr int widen_plan(int sl, int which)
+{
+    constexpr int NM = 4 * FM;
+    constexpr int carry[5] = {0, 4, 5, 6, 7};                       // a0, b0, b1, b2, b3
+    if (FM == 4) {
+        constexpr int hi_order[8] = {4, 0, 5, 6, 7, 1, 2, 3};       // b0 a0 b1 b2 b3 a1 a2 a3
+        if (which != 0) return 0;
+        if (sl < 6) return ((sl & 1) ? W_AN : W_SH) * 8 + 1 + sl / 2;
+        if (sl < 14) return W_HI * 8 + hi_order[sl - 6];
+        if (sl < NM + 6) return 0;
+        return (((sl - NM) & 1) ? W_AN : W_SHN) * 8 + carry[(sl - NM - 6) / 2];
+    } else {
+        constexpr int hi_order[6] = {4, 0, 5, 6, 7, 1};
+        if (sl < 2) return which ? 0 : (sl ? W_AN : W_SH) * 8 + 1;
+        if (sl < NM) return which ? 0 : W_HI * 8 + hi_order[sl - 2];
+        if (sl < NM + 3) return 0;
+        return (which ? W_AN : W_SHN) * 8 + carry[sl - NM - 3];
+    }
+}
+
 template <int MODE, int BM, int BN, bool ONLY_BF16, int W>
 __device__ __forceinline__ void gemm_deep_tile(uint8_t* smem, int m0, int n0, const uint8_t* __restrict__ A,
                                                const uint8_t* __restrict__ B, int M, int N, int rowbytes,
@@ -1030,7 +1056,7 @@ __device__ __forceinline__ void gemm_deep_tile(uint8_t* smem, int m0, int n0, co
                                                void* __restrict__ Y, int y_dtype, int ldy,
                                                const float* __restrict__ bias)
 {
-    static_assert(MODE == MODE_I8 || MODE == MODE_BF16, "16-byte operands per lane");
+    static_assert(MODE == MODE_I8 || MODE == MODE_BF16 || MODE == MODE_I4, "16-byte operands per lane");
     constexpr int WM = 2, WN = 2, NW = 4, BKB = 128;
     constexpr int CPR = BKB / 16, RPB = 64 / CPR;
     constexpr int A_BLOCKS = BM / RPB / NW, B_BLOCKS = BN / RPB / NW;
@@ -1094,28 +1120,66 @@ __device__ __forceinline__ void gemm_deep_tile(uint8_t* smem, int m0, int n0, co
     // other buffer; and this wave's copies of the slice.  kind: 0 none, 1 = B blocks [B_BLOCKS/2, B_BLOCKS),
     // 2 = A blocks [0, A_BLOCKS/2), 3 = A blocks [A_BLOCKS/2, A_BLOCKS), 4 = B blocks [0, B_BLOCKS/2); C copies in
     // NM slots, one every S = NM / C slots, this wave's at offset W mod S.
+    // Packed nibbles (MODE_I4): a slice is 32 packed bytes of k = two MFMA k-steps, a low pass over the NM
+    // accumulators with the low nibbles (x << 4) & 0xf0.. (alo / blo) and a high pass with the high nibbles
+    // x & 0xf0.., formed in place in the packed registers.  The LDS reads of the next slice are issued in the high
+    // pass (issued in the low pass, with their results waiting a whole pass, they cost a quarter of the MFMA rate:
+    // measured).  The widening runs in the shadow of the MFMAs, at most widen_plan's steps per MFMA slot, each at
+    // least one slot before its first use; a slice enters with alo[0] and blo[0..3] ready: formed during the high
+    // pass of the slice before (in the prologue for the first).
+    v4i alo[FM], blo[FN];
+    auto widen_lo = [](const v4i& x) -> v4i { return (x << 4) & (int)0xf0f0f0f0; };
+    // One widening step = 4 VALU instructions on one operand vector: W_SH lo = packed << 4 (W_SHN: of the NEXT slice's
+    // packed vector), W_AN lo &= 0xf0.., W_HI packed &= 0xf0.. in place (after the vector's W_SH).
+    auto widen_step = [&](int code, int cur) {
+        const int kind = code >> 3, x = code & 7, src = (kind == W_SHN) ? (cur ^ 1) : cur;
+        if (kind == W_SH || kind == W_SHN) {
+            if (x < 4) alo[x] = opa[src][x] << 4;
+            else blo[x - 4] = opb[src][x - 4] << 4;
+        } else if (kind == W_AN) {
+            if (x < 4) alo[x] = alo[x] & (int)0xf0f0f0f0;
+            else blo[x - 4] = blo[x - 4] & (int)0xf0f0f0f0;
+        } else if (kind == W_HI) {
+            if (x < 4) opa[cur][x] = opa[cur][x] & (int)0xf0f0f0f0;
+            else opb[cur][x - 4] = opb[cur][x - 4] & (int)0xf0f0f0f0;
+        }
+    };
     auto slice = [&](int cur, const uint8_t* ra, const uint8_t* rb, int rks, auto rd_tag, auto kind_tag, int copy_stage,
                      int copy_slot) {
         constexpr bool rd = decltype(rd_tag)::value;
         constexpr int kind = decltype(kind_tag)::value;
         constexpr int C = (kind == 0) ? 0 : ((kind == 2 || kind == 3) ? A_BLOCKS / 2 : B_BLOCKS / 2);
-        constexpr int S = (C == 0) ? 1 : NM / C;
-        static_assert(C == 0 || (NM % C == 0 && S >= 1), "copies must tile the MFMA slots");
+        constexpr int SLOTS = (MODE == MODE_I4) ? 2 * NM : NM;        // MFMA slots of the slice
+        constexpr int S = SLOTS / (C == 0 ? SLOTS : C);
+        static_assert(C == 0 || (SLOTS % C == 0 && S >= 1), "copies must tile the MFMA slots");
+        static_assert(MODE != MODE_I4 || (FN == 4 && (FM == 4 || FM == 2)), "widening plans exist for these tiles");
 #pragma unroll
-        for (int t = 0; t < NM; ++t) {
-            const int i = t / FN, j = t % FN;
-            if constexpr (MODE == MODE_I8)
+        for (int sl = 0; sl < SLOTS; ++sl) {
+            const int t = sl % NM, i = t / FN, j = t % FN;
+            if constexpr (MODE == MODE_I8) {
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opb[cur][j], opa[cur][i], acc[i][j], 0, 0, 0);
-            else
+            } else if constexpr (MODE == MODE_I4) {
+                if (sl < NM) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[j], alo[i], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opb[cur][j], opa[cur][i], acc[i][j], 0, 0, 0);
+                if (sl < NM || rd) {
+                    widen_step(widen_plan<FM>(sl, 0), cur);
+                    widen_step(widen_plan<FM>(sl, 1), cur);
+                }
+            } else {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, opb[cur][j]),
                                                                    __builtin_bit_cast(v8bf, opa[cur][i]), acc[i][j], 0, 0, 0);
+            }
             if constexpr (rd) {
+                if constexpr (MODE == MODE_I4) {
+                    if (sl >= NM && t < NR) read_op(ra, rb, rks, cur ^ 1, t);     // one read per slot from the high pass on
+                } else {
 #pragma unroll
-                for (int q = t * NR / NM; q < (t + 1) * NR / NM; ++q) read_op(ra, rb, rks, cur ^ 1, q);
+                    for (int q = t * NR / NM; q < (t + 1) * NR / NM; ++q) read_op(ra, rb, rks, cur ^ 1, q);
+                }
             }
             if constexpr (C != 0) {
-                if (t % S == W % S) {
-                    const int q = t / S;
+                if (sl % S == (W * (S / 4 > 0 ? S / 4 : 1)) % S) {
+                    const int q = sl / S;
                     if constexpr (kind == 1) issue_b(copy_stage, copy_slot, B_BLOCKS / 2 + q);
                     else if constexpr (kind == 2) issue_a(copy_stage, copy_slot, q);
                     else if constexpr (kind == 3) issue_a(copy_stage, copy_slot, A_BLOCKS / 2 + q);
@@ -1151,6 +1215,11 @@ __device__ __forceinline__ void gemm_deep_tile(uint8_t* smem, int m0, int n0, co
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_op(smem, smem + B_BASE, 0, 0, r);
+    if constexpr (MODE == MODE_I4) {
+        alo[0] = widen_lo(opa[0][0]);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) blo[j] = widen_lo(opb[0][j]);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     int ia = 0, ib = 0;                              // ring slots of the stage being multiplied
@@ -1663,18 +1732,25 @@ int launch_reg(const void* A, const void* B, int M, int N, int rowbytes, const f
     return FQ_OK;
 }
 
+// gemm_wide_kernel has no packed-nibble form: only the deep kernel is instantiated for MODE_I4
+template <int MODE, bool DEEP>
+auto pick_wide_kernel(bool only_bf16)
+{
+    if constexpr (DEEP) return only_bf16 ? gemm_deep_kernel<MODE, true> : gemm_deep_kernel<MODE, false>;
+    else return only_bf16 ? gemm_wide_kernel<MODE, true> : gemm_wide_kernel<MODE, false>;
+}
+
 template <int MODE, bool DEEP = false>
 int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w, void* Y,
                 int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {
-    if constexpr (MODE == MODE_I8 || MODE == MODE_BF16) {
+    if constexpr (MODE == MODE_I8 || MODE == MODE_BF16 || (MODE == MODE_I4 && DEEP)) {
         if ((unsigned long long)M * rowbytes >= (1ull << 32) || (unsigned long long)N * rowbytes >= (1ull << 32))
             return fail(FQ_ERR_RANGE, "operand larger than 4 GiB");
         if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variants 11 and 12 need rows of whole 128-byte stages");
         // the common case (bf16 output, no bias) has an instantiation with that epilogue only
         const bool only_bf16 = y_dtype == FQ_BF16 && !bt.bias;
-        auto kern = DEEP ? (only_bf16 ? gemm_deep_kernel<MODE, true> : gemm_deep_kernel<MODE, false>)
-                         : (only_bf16 ? gemm_wide_kernel<MODE, true> : gemm_wide_kernel<MODE, false>);
+        auto kern = pick_wide_kernel<MODE, DEEP>(only_bf16);
         // two stage buffers of 64 KiB, or (deep) three A and two B buffers of 32 KiB: all of the CU's LDS
         constexpr int smem = DEEP ? 5 * 256 * 128 : 2 * 512 * 128;
         static std::atomic<unsigned long long> attr_set[2];
@@ -1697,7 +1773,7 @@ int launch_wide(const void* A, const void* B, int M, int N, int rowbytes, const 
         if (e != hipSuccess) return fail(FQ_ERR_HIP, "GEMM launch failed: %s", hipGetErrorString(e));
         return FQ_OK;
     } else {
-        return fail(FQ_ERR_RANGE, "GEMM variants 11 and 12 exist for INT8 and bf16 operands only");
+        return fail(FQ_ERR_RANGE, "GEMM variant 11 exists for INT8 and bf16 operands only, 12 also for packed nibbles");
     }
 }
 
@@ -1714,11 +1790,11 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
         // k-slices per phase and spill, so they keep two k-slices per phase (7), as do reductions of
         // only a few k-stages (attention's Q K^T)
         v = (big_tiles >= 192 && N > 128) ? ((MODE == MODE_I4 && rowbytes >= 512) ? 10 : 7) : 6;
-        // INT8 and bf16 with rows of whole 128-byte stages, bf16 output and no bias (the instantiation with
-        // that epilogue only): the four-wave kernel with the deep staging (+14 % over the ping-pong kernel at full
-        // clock, +3-5 % at the clock the power limit leaves on live operands)
-        if ((MODE == MODE_BF16 || MODE == MODE_I8) && v == 7 && rowbytes % 128 == 0 && bt.count == 1 &&
-            y_dtype == FQ_BF16 && !bt.bias)
+        // rows of whole 128-byte stages, bf16 output and no bias (the instantiation with that epilogue only): the
+        // four-wave kernel with the deep staging (INT8 and bf16: +14 % over the ping-pong kernel at full clock,
+        // +3-5 % at the clock the power limit leaves on live operands; packed nibbles: +1-5 % on live operands)
+        if ((v == 7 || v == 10) && MODE != MODE_F6 && rowbytes % 128 == 0 && bt.count == 1 && y_dtype == FQ_BF16 &&
+            !bt.bias)
             v = 12;
     }
     switch (v) {

@@ -31,7 +31,7 @@ int check_forced_variant(int bits, int rowbytes)
 {
     if (g_variant != 11 && g_variant != 12) return FQ_OK;
     if (bits == FQ_BITS_I4_E3M2) return FQ_OK;              // the 6-bit GEMM has one kernel and ignores the hook
-    if (bits != 8) return fail(FQ_ERR_RANGE, "GEMM variants 11 and 12 exist for INT8 and bf16 operands only");
+    if (bits != 8 && g_variant == 11) return fail(FQ_ERR_RANGE, "GEMM variant 11 exists for INT8 and bf16 operands only");
     if (rowbytes % 128) return fail(FQ_ERR_SHAPE, "GEMM variants 11 and 12 need rows of whole 128-byte stages");
     return FQ_OK;
 }

@@ -712,17 +712,57 @@ def test_gemm_four_wave_kernel_int8(variant):
         fq.fq_gemm_select(-1)
 
 
-@pytest.mark.parametrize("variant", [11, 12])
-def test_gemm_four_wave_kernel_rejects_nibbles_and_partial_stages(variant):
-    fq.fq_gemm_select(variant)
+def test_gemm_four_wave_kernel_nibbles():
+    """Variant 12 on packed nibbles (low pass / high pass per k-slice, widening interleaved with the MFMAs): raw
+    accumulators on ragged shapes with one, two, three and more k-stages, the extreme codes at the longest row that the
+    accumulator bound allows, a grid with half-height tail tiles, the bf16 epilogue with bias, a batched launch."""
+    rng = np.random.default_rng(1300)
+    fq.fq_gemm_select(12)
     try:
-        Xq = torch.zeros((4, 16), dtype=torch.uint8, device=DEV)
-        Y = torch.zeros((4, 4), dtype=torch.int32, device=DEV)
-        with pytest.raises(fq.FqError, match="FQ_ERR_RANGE"):
+        for (M, N, Kpad) in [(300, 520, 768), (257, 129, 2304), (1, 1, 256), (33, 700, 512), (512, 256, 1280), (70, 41, 3328),
+                             (17 * 256 - 20, 16 * 256 - 7, 512)]:
+            Xq, Wq = _rand_q(rng, M, Kpad, 4), _rand_q(rng, N, Kpad, 4)
+            assert np.array_equal(_gemm_acc(Xq, Wq, 4), O.gemm_i32(Xq, Wq)), (M, N, Kpad)
+        Xq = np.full((40, 65536), -8, np.int8)
+        Wq = np.full((70, 65536), -8, np.int8)
+        Wq[1::2] = 7
+        Xq[:, 1::2] = 7                                             # low and high nibbles differ in every byte
+        assert np.array_equal(_gemm_acc(Xq, Wq, 4), O.gemm_i32(Xq, Wq))
+        M, N, Kpad = 300, 333, 1024
+        Xq, Wq = _rand_q(rng, M, Kpad, 4), _rand_q(rng, N, Kpad, 4)
+        s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+        bias = rng.normal(0, 3.0, N).astype(np.float32)
+        Ybuf = torch.full((M, 384), 7.0, dtype=torch.bfloat16, device=DEV)
+        fq.fq_gemm_i4_bias(torch.from_numpy(O.pack_i4(Xq)).to(DEV), torch.from_numpy(O.pack_i4(Wq)).to(DEV), scalar(s_x),
+                           scalar(s_w), torch.from_numpy(bias).to(DEV), Ybuf[:, :N])
+        torch.cuda.synchronize()
+        want = O.dequant_out(O.gemm_i32(Xq, Wq), s_x, s_w, "bf16", bias)
+        assert np.array_equal(bits16(Ybuf[:, :N]), want)
+        assert (Ybuf[:, N:].float() == 7.0).all()
+        Aq, Bq = _bmm_operands(9, 3, 260, 300, 512, 4)
+        Y = torch.full((3, 260, 300), -1, dtype=torch.int32, device=DEV)
+        fq.fq_bmm_i4(_to_dev_q(Aq, 4), _to_dev_q(Bq, 4), None, None, Y)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy(), O.bmm_i32(Aq, Bq))
+    finally:
+        fq.fq_gemm_select(-1)
+
+
+def test_gemm_four_wave_kernels_reject_what_they_cannot_run():
+    Y = torch.zeros((4, 4), dtype=torch.int32, device=DEV)
+    try:
+        fq.fq_gemm_select(11)
+        Xq = torch.zeros((4, 128), dtype=torch.uint8, device=DEV)
+        with pytest.raises(fq.FqError, match="FQ_ERR_RANGE"):              # no packed-nibble form of variant 11
             fq.fq_gemm_i4(Xq, Xq, None, None, Y)
-        X8 = torch.zeros((4, 160), dtype=torch.int8, device=DEV)          # 160-byte rows: a partial second stage
+        for variant in (11, 12):
+            fq.fq_gemm_select(variant)
+            X8 = torch.zeros((4, 160), dtype=torch.int8, device=DEV)      # 160-byte rows: a partial second stage
+            with pytest.raises(fq.FqError, match="FQ_ERR_SHAPE"):
+                fq.fq_gemm_i8(X8, X8, None, None, Y)
+        X4 = torch.zeros((4, 80), dtype=torch.uint8, device=DEV)          # 160 nibbles: less than one stage
         with pytest.raises(fq.FqError, match="FQ_ERR_SHAPE"):
-            fq.fq_gemm_i8(X8, X8, None, None, Y)
+            fq.fq_gemm_i4(X4, X4, None, None, Y)
     finally:
         fq.fq_gemm_select(-1)
 
