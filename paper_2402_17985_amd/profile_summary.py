@@ -1,0 +1,133 @@
+"""Turn rocprofv3 CSV output of `bench.py` into the short summaries kept under profiles/.
+
+    python -m paper_2402_17985_amd.profile_summary stats   <dir> <out.txt>  "<command that made dir>"
+    python -m paper_2402_17985_amd.profile_summary pmc     <dir> <out.txt>  "<command that made dir>"
+    python -m paper_2402_17985_amd.profile_summary traffic <fetch dir> <write dir> <out.txt> <out.json> "<commands>"
+
+stats:   per-kernel call count, total and average duration from a `--kernel-trace --stats` run.
+pmc:     per-kernel mean of every counter of a `--pmc` run.
+traffic: HBM-side bytes per launch of the dominant GEMM kernel from a FETCH_SIZE run and a WRITE_SIZE run of
+         `bench.py --copy-ref` (counters in KiB per dispatch), each scaled by what the same counter reads for the
+         copy kernel of known size in the same run (1 GiB read, 1 GiB written per launch).  Writes the figures
+         together with the hash of the kernel sources they belong to; bench.py reports them as roofline.traffic
+         only while that hash matches the tree.
+
+Only reads CSV files and writes text; runs nothing."""
+import collections
+import csv
+import glob
+import hashlib
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GIB = float(1 << 30)
+
+
+def kernel_sources_sha():
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2402_17985_amd", "csrc", "*"))):
+        if os.path.isfile(f):
+            h.update(os.path.basename(f).encode())
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _find(d, suffix):
+    files = glob.glob(os.path.join(d, "**", "*" + suffix), recursive=True)
+    if not files:
+        raise SystemExit(f"no *{suffix} under {d}")
+    return files
+
+
+def short(name, n=72):
+    name = name.replace("fq::(anonymous namespace)::", "").replace("void ", "")
+    return name[:n]
+
+
+def kernel_durations(d):
+    """{kernel: [durations in ns]} from the kernel trace."""
+    out = collections.defaultdict(list)
+    for f in _find(d, "kernel_trace.csv"):
+        for r in csv.DictReader(open(f)):
+            out[r["Kernel_Name"]].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    return out
+
+
+def counters(d):
+    """{kernel: {counter: [values per dispatch]}}"""
+    out = collections.defaultdict(lambda: collections.defaultdict(list))
+    for f in _find(d, "counter_collection.csv"):
+        for r in csv.DictReader(open(f)):
+            out[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return out
+
+
+def cmd_stats(d, out, command):
+    dur = kernel_durations(d)
+    total = sum(sum(v) for v in dur.values())
+    lines = [f"# {command}", "# per kernel: calls, total ms, average us, share of GPU kernel time", ""]
+    for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
+        if sum(v) < 0.002 * total:
+            continue
+        lines.append(f"{len(v):7d} {sum(v) / 1e6:10.3f} ms {sum(v) / len(v) / 1e3:10.2f} us {100.0 * sum(v) / total:6.2f} %  {short(k)}")
+    open(out, "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
+def cmd_pmc(d, out, command):
+    lines = [f"# {command}", "# per kernel: mean of each counter over its dispatches", ""]
+    for k, c in sorted(counters(d).items()):
+        n = max(len(v) for v in c.values())
+        lines.append(f"{short(k)}  ({n} dispatches)")
+        for name, v in sorted(c.items()):
+            lines.append(f"    {name:34s} {sum(v) / len(v):16.5g}")
+    open(out, "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
+def _mean(c, kernel_substr, counter):
+    vals = [x for k, cc in c.items() if kernel_substr in k for x in cc.get(counter, [])]
+    return (sum(vals) / len(vals), len(vals)) if vals else (None, 0)
+
+
+def cmd_traffic(fetch_dir, write_dir, out, out_json, command):
+    cf, cw = counters(fetch_dir), counters(write_dir)
+    copy_f, nf = _mean(cf, "copy_kernel", "FETCH_SIZE")
+    copy_w, nw = _mean(cw, "copy_kernel", "WRITE_SIZE")
+    if not copy_f or not copy_w:
+        raise SystemExit("the runs hold no copy_kernel dispatches: run bench.py with --copy-ref")
+    f_scale = GIB / (copy_f * 1024.0)
+    w_scale = GIB / (copy_w * 1024.0)
+    lines = [f"# {command}",
+             f"# copy kernel of 1 GiB read + 1 GiB written: FETCH_SIZE reads {copy_f:.0f} KiB ({nf} launches) -> factor {f_scale:.3f};"
+             f" WRITE_SIZE reads {copy_w:.0f} KiB ({nw} launches) -> factor {w_scale:.3f}", ""]
+    rec = {"kernel_sources_sha": kernel_sources_sha(), "fetch_factor": round(f_scale, 4), "write_factor": round(w_scale, 4),
+           "command": command, "bytes_per_launch": {}, "kernels": {}}
+    for key, sub in (("cfg3,cfg3i8:nibble", "gemm_deep_kernel<1"), ("cfg3,cfg3i8:e3m2", "gemm_f6_wide_kernel"),
+                     ("int8", "gemm_deep_kernel<0")):
+        f, n1 = _mean(cf, sub, "FETCH_SIZE")
+        w, n2 = _mean(cw, sub, "WRITE_SIZE")
+        if f is None or w is None:
+            continue
+        fb, wb = f * 1024.0 * f_scale, w * 1024.0 * w_scale
+        lines.append(f"{sub:24s} {n1:4d} launches: fetch {fb / 1e6:9.1f} MB  write {wb / 1e6:9.1f} MB  total {(fb + wb) / 1e6:9.1f} MB per launch")
+        rec["kernels"][sub] = {"fetch_bytes": round(fb), "write_bytes": round(wb), "launches": n1}
+        if ":" in key:
+            rec["bytes_per_launch"][key] = round(fb + wb)
+    open(out, "w").write("\n".join(lines) + "\n")
+    json.dump(rec, open(out_json, "w"), indent=1)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    a = sys.argv[1:]
+    if len(a) == 4 and a[0] == "stats":
+        cmd_stats(a[1], a[2], a[3])
+    elif len(a) == 4 and a[0] == "pmc":
+        cmd_pmc(a[1], a[2], a[3])
+    elif len(a) == 6 and a[0] == "traffic":
+        cmd_traffic(a[1], a[2], a[3], a[4], a[5])
+    else:
+        raise SystemExit(__doc__)

@@ -679,7 +679,7 @@ def test_gemm_four_wave_kernel_int8(variant):
     fq.fq_gemm_select(variant)
     try:
         for (M, N, Kpad) in [(300, 520, 384), (257, 129, 1152), (1, 1, 128), (33, 700, 256), (512, 256, 128), (70, 41, 640),
-                             (17 * 256 - 20, 16 * 256 - 7, 256)]:
+                             (17 * 256 - 20, 16 * 256 - 7, 256), (24 * 256 - 20, 22 * 256 - 7, 384)]:
             Xq, Wq = _rand_q(rng, M, Kpad, 8), _rand_q(rng, N, Kpad, 8)
             assert np.array_equal(_gemm_acc(Xq, Wq, 8), O.gemm_i32(Xq, Wq)), (M, N, Kpad)
         lo = -128
@@ -720,7 +720,7 @@ def test_gemm_four_wave_kernel_nibbles():
     fq.fq_gemm_select(12)
     try:
         for (M, N, Kpad) in [(300, 520, 768), (257, 129, 2304), (1, 1, 256), (33, 700, 512), (512, 256, 1280), (70, 41, 3328),
-                             (17 * 256 - 20, 16 * 256 - 7, 512)]:
+                             (17 * 256 - 20, 16 * 256 - 7, 512), (24 * 256 - 20, 22 * 256 - 7, 768)]:
             Xq, Wq = _rand_q(rng, M, Kpad, 4), _rand_q(rng, N, Kpad, 4)
             assert np.array_equal(_gemm_acc(Xq, Wq, 4), O.gemm_i32(Xq, Wq)), (M, N, Kpad)
         Xq = np.full((40, 65536), -8, np.int8)
@@ -746,6 +746,29 @@ def test_gemm_four_wave_kernel_nibbles():
         assert np.array_equal(Y.cpu().numpy(), O.bmm_i32(Aq, Bq))
     finally:
         fq.fq_gemm_select(-1)
+
+
+@pytest.mark.parametrize("bits,Kpad", [(8, 128), (8, 256), (8, 640), (4, 256), (4, 512), (4, 1280)])
+def test_gemm_four_wave_kernel_several_rounds_bf16(bits, Kpad):
+    """More than two rounds of whole tiles per CU plus half-height tail tiles, bf16 output, reductions of one, two
+    and five stages (packed nibbles: a stage is 256 values).  Every stored bf16 against the oracle's bits."""
+    rng = np.random.default_rng(1400 + bits + Kpad)
+    M, N = 27 * 256, 21 * 256 + 128                         # 27 x 22 = 594 tiles: 512 whole + 82 -> 164 halves
+    Xq, Wq = _rand_q(rng, M, Kpad, bits), _rand_q(rng, N, Kpad, bits)
+    s_x, s_w = np.float32(0.0123), np.float32(0.00071)
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    fq.fq_gemm_select(12)
+    try:
+        (fq.fq_gemm_i8 if bits == 8 else fq.fq_gemm_i4)(_to_dev_2d(Xq, bits), _to_dev_2d(Wq, bits), scalar(s_x), scalar(s_w), Y)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_gemm_select(-1)
+    want = O.dequant_out(O.gemm_i32(Xq, Wq), s_x, s_w, "bf16")
+    assert np.array_equal(bits16(Y), want)
+
+
+def _to_dev_2d(q, bits):
+    return torch.from_numpy(q if bits == 8 else O.pack_i4(q)).to(DEV)
 
 
 def test_gemm_four_wave_kernels_reject_what_they_cannot_run():
