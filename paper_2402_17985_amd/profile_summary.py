@@ -3,6 +3,7 @@
     python -m paper_2402_17985_amd.profile_summary stats   <dir> <out.txt>  "<command that made dir>"
     python -m paper_2402_17985_amd.profile_summary pmc     <dir> <out.txt>  "<command that made dir>"
     python -m paper_2402_17985_amd.profile_summary traffic <fetch dir> <write dir> <out.txt> <out.json> "<commands>"
+    python -m paper_2402_17985_amd.profile_summary table   <out.txt> <bench line>.json [...] [--static <bench line>.json ...]
 
 stats:   per-kernel call count, total and average duration from a `--kernel-trace --stats` run.
 pmc:     per-kernel mean of every counter of a `--pmc` run.
@@ -12,7 +13,9 @@ traffic: HBM-side bytes per launch of the dominant GEMM kernel from a FETCH_SIZE
          together with the hash of the kernel sources they belong to; bench.py reports them as roofline.traffic
          only while that hash matches the tree.
 
-Only reads CSV files and writes text; runs nothing."""
+table:   one row per layer out of the JSON lines that `bench.py --configs <cfg>` printed (one file per run).
+
+Only reads CSV / JSON files and writes text; runs nothing."""
 import collections
 import csv
 import glob
@@ -121,6 +124,41 @@ def cmd_traffic(fetch_dir, write_dir, out, out_json, command):
     print("\n".join(lines))
 
 
+def cmd_table(out, files, static_files):
+    L = ["bench.py on the configurations of BASELINE.json (one MI355X; HIP-event timings inside bench.py; dynamic per-tensor",
+         "activation scale unless marked static; bf16 output; Kpad padded to 128 channels (256 for packed nibbles)).",
+         "4-bit layers as packed nibbles on the int8 MFMA; 'e3m2 us' / 'e3m2 TOPS' = the same layer's GEMM in E3M2 storage on the 6-bit MFMA.",
+         "commands (from the repository root):  python3 bench.py --no-cpu --no-peak --configs <cfg> --steps 50 --warmup 30   [--static]",
+         "gemm TOPS = 2*M*Kpad*N / t_gemm (%peak: of the 5.0 POP/s int8 MFMA peak); clk = shader clock during the GEMM (MHz);",
+         "fq GB/s = algorithmic bytes of absmax + flatten-quantize / their time; lin = whole fq_linear; bf16 = in-library bf16 MFMA GEMM",
+         "at the unflattened K; vendor = torch.matmul on the same operands; speedup = min(t bf16, t vendor) / t(fq_linear).", "",
+         f"{'layer':20s} {'bits':>4s} {'M':>6s} {'K':>6s} {'N':>6s} {'Kpad':>6s} {'fq us':>8s} {'fq GB/s':>8s} {'gemm us':>8s} {'gemm TOPS':>9s} "
+         f"{'%peak':>6s} {'clk':>5s} {'lin us':>8s} {'bf16 us':>8s} {'vendor us':>9s} {'speedup':>7s} {'e3m2 us':>8s} {'e3m2 TOPS':>9s}"]
+
+    def rows(fn, tag=""):
+        d = json.loads(open(fn).read().strip().split("\n")[-1])
+        for r in d["layers"]:
+            o = r.get("other_storage") or {}
+            L.append(f"{r['layer'] + tag:20s} {r['bits']:4d} {r['M']:6d} {r['K']:6d} {r['N']:6d} {r['Kpad']:6d} "
+                     f"{r['ms_flatten_quant'] * 1e3:8.1f} {r['flatten_quant_gbs']:8.0f} {r['ms_gemm'] * 1e3:8.1f} {r['gemm_tops']:9.0f} "
+                     f"{r['gemm_pct_int8_peak']:6.1f} {r.get('gemm_clock_mhz', 0):5.0f} {r['ms_linear'] * 1e3:8.1f} {r['ms_gemm_bf16'] * 1e3:8.1f} "
+                     f"{r.get('ms_vendor_bf16', 0) * 1e3:9.1f} {r['speedup_vs_bf16']:7.3f} {o.get('ms_gemm', 0) * 1e3:8.1f} {o.get('gemm_tops', 0):9.0f}")
+        return d
+
+    steps = []
+    for fn in files:
+        d = rows(fn)
+        steps.append(f"  {d['config']['layers']}: {d['ms_per_step']:.4f} ms per step, {d['value']:.0f} TOPS executed, "
+                     f"{d['effective_tops']:.0f} TOPS effective (unflattened K), speedup {d['speedup_vs_bf16']:.3f}")
+    if static_files:
+        L += ["", "static activation scale a' = T (the paper's mode: no absmax pass)"]
+        for fn in static_files:
+            rows(fn, " (static)")
+    L += ["", "whole-step figures (value = sum of 2*M*Kpad*N over the run's layers / step time):"] + steps
+    open(out, "w").write("\n".join(L) + "\n")
+    print("\n".join(L))
+
+
 if __name__ == "__main__":
     a = sys.argv[1:]
     if len(a) == 4 and a[0] == "stats":
@@ -129,5 +167,9 @@ if __name__ == "__main__":
         cmd_pmc(a[1], a[2], a[3])
     elif len(a) == 6 and a[0] == "traffic":
         cmd_traffic(a[1], a[2], a[3], a[4], a[5])
+    elif len(a) >= 3 and a[0] == "table":
+        rest = a[2:]
+        k = rest.index("--static") if "--static" in rest else len(rest)
+        cmd_table(a[1], rest[:k], rest[k + 1:])
     else:
         raise SystemExit(__doc__)
