@@ -179,3 +179,28 @@ def test_plan_xw_matches_oracle(seed):
         fq.fq_flatten_plan_xw(cx, 0.0)
     with pytest.raises(fq.FqError):
         fq.fq_flatten_plan_xw(cx, 1.0, cw, float("inf"))
+
+
+def test_runtime_failures_come_back_as_fq_err_hip():
+    """Error path of the device calls, forced from the host: on a machine without a GPU every HIP call fails, and the
+    entry points must hand that back as FQ_ERR_HIP with the runtime's message (no crash, nothing thrown across the
+    C boundary).  With a GPU present these calls would launch on dummy pointers, so the test runs only without one."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("needs a machine without a GPU: the failing runtime is the forced condition")
+    L = fq.lib()
+    dummy = 0x10000
+    ws = fq.fq_act_workspace_bytes(64, 64)
+    calls = [
+        lambda: L.fq_gemm_i8(dummy, dummy, 4, 4, 32, dummy, dummy, dummy, fq.FQ_F32, 4, None),
+        lambda: L.fq_gemm_i4(dummy, dummy, 4, 4, 32, dummy, dummy, dummy, fq.FQ_BF16, 8, None),
+        lambda: L.fq_flatten_quant_act(dummy, fq.FQ_BF16, 4, 64, 64, dummy, dummy, 64, 8, None, dummy, dummy, dummy, ws, None),
+        lambda: L.fq_flatten_quant_act_noalloc(dummy, fq.FQ_BF16, 4, 64, 64, dummy, dummy, 64, 8, None, dummy, dummy, None),
+        lambda: L.fq_channel_absmax(dummy, fq.FQ_BF16, 4, 64, 64, 0, dummy, None),
+        lambda: L.fq_gemm_bf16(dummy, dummy, 4, 4, 16, dummy, 4, None),
+    ]
+    for call in calls:
+        assert call() == 6                                   # FQ_ERR_HIP
+        assert L.fq_last_error_string()                     # the runtime's own message is kept
+    with pytest.raises(fq.FqError, match="FQ_ERR_HIP"):
+        fq.binding._check(calls[0]())
