@@ -118,6 +118,8 @@ def main():
                     help="also run one plain 1 GiB device copy at the end (the reference kernel for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-bmm", action="store_true", help="skip the attention-shaped batched-product rows")
+    ap.add_argument("--fused", action="store_true",
+                    help="also time fq_linear_fused_a_i8 against quantize-then-GEMM on the INT8 layers of cfg3i8 and cfg5")
     ap.add_argument("--e3m2", action="store_true",
                     help="time the 4-bit layers as E3M2 codes on the 6-bit MFMA instead of packed nibbles on the int8 MFMA")
     ap.add_argument("--no-alt", action="store_true", help="do not also measure the 4-bit storage that is not timed")
@@ -462,6 +464,41 @@ def main():
                 log("[kernel] " + json.dumps(row))
                 del Aq, Bq, Yb
 
+    # ---------------- flatten + quantize fused into the GEMM's A-operand load (on request) ----------------
+    # The INT8 layer three ways on the same inputs: the default path (quantize, then the large-problem GEMM), the same
+    # two steps with the GEMM forced to the 128 x 128 register-staged kernel (the structure the fused kernel shares),
+    # and fq_linear_fused_a_i8, which reads X in the GEMM.  Static and dynamic activation scale.
+    fused_rows = []
+    if args.fused:
+        for cname, idx in (("cfg3i8", 0), ("cfg5", 1)):
+            Lf = WL.make_layer(WL.CONFIGS[cname], idx)
+            sp = Lf.spec
+            layf = fq.FqLinear(torch.from_numpy(Lf.W_store.view(np.int16)).to(dev).view(torch.bfloat16), Lf.chmax, Lf.T, 8, device=dev)
+            Xf = torch.from_numpy(Lf.X_store.view(np.int16)).to(dev).view(torch.bfloat16)
+            Yf = torch.empty((sp.M, sp.N), dtype=torch.bfloat16, device=dev)
+            Yg = torch.empty_like(Yf)
+            wsf = torch.empty(fq.fq_linear_workspace_bytes(sp.M, sp.K, layf.Kpad, 8), dtype=torch.uint8, device=dev)
+            for static in (False, True):
+                a_in = torch.full((1,), float(Lf.T), dtype=torch.float32, device=dev) if static else None
+                unfused = lambda: fq.fq_linear(Xf, layf.src, layf.rep, layf.Wq, layf.s_w, 8, Yf, wsf, absmax_in=a_in)
+                fused = lambda: fq.fq_linear_fused_a_i8(Xf, layf.src, layf.rep, layf.Wq, layf.s_w, Yg, wsf, absmax_in=a_in)
+                t_default = event_time_ms(unfused, args.steps)
+                fq.fq_gemm_select(2)
+                try:
+                    t_same = event_time_ms(unfused, max(args.steps // 4, 5))
+                finally:
+                    fq.fq_gemm_select(args.variant)
+                t_fused = event_time_ms(fused, max(args.steps // 4, 5))
+                unfused()
+                fused()
+                torch.cuda.synchronize()
+                row = dict(layer=f"{cname}.{sp.name}", M=sp.M, K=sp.K, N=sp.N, Kpad=layf.Kpad, scale="static" if static else "dynamic",
+                           ms_quantize_then_gemm=round(t_default, 4), ms_quantize_then_gemm_same_tile=round(t_same, 4),
+                           ms_fused=round(t_fused, 4), outputs_identical=bool(torch.equal(Yf.view(torch.int16), Yg.view(torch.int16))))
+                fused_rows.append(row)
+                log("[fused] " + json.dumps(row))
+            del Lf, layf, Xf, Yf, Yg, wsf
+
     if args.copy_ref:
         src_buf = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst_buf = torch.empty_like(src_buf)
@@ -552,6 +589,7 @@ def main():
         "cpu_baseline": cpu,
         "layers": rows,
         "bmm": bmm_rows,
+        "fused_a_operand": fused_rows,
     }
     print(json.dumps(out), flush=True)
 

@@ -335,6 +335,22 @@ int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx,
 size_t fq_linear_workspace_bytes(int M, int K, int Kpad, int bits);
 
 /* ---------------------------------------------------------------------------------------------
+ * fq_linear_fused_a_i8 — the INT8 layer with flatten + quantize fused into the GEMM's A-operand load (Sec. 6,
+ * named there as future work): fq_linear_bias for bits = 8 without the quantized activation ever being written to
+ * memory.  The scale (static *absmax_in, or NULL = dynamic: one absmax pass over X) and the per-slot multipliers
+ * are formed first; the GEMM then reads X itself and quantizes slot p of a row from X[row, src_idx[p]] on the way
+ * into LDS, with the arithmetic of fq_flatten_quant_act.  Results are identical to fq_linear_bias, bit for bit,
+ * for every output type.  Every 128-column tile of the output converts its rows of X again, inside the MFMA loop:
+ * measured 2.4 to 4.8 times slower than fq_linear_bias at every shape tried (narrow outputs included).  It is
+ * the measured answer to that future-work item, not a path to prefer.
+ * X bf16 only (FQ_ERR_DTYPE otherwise); workspace >= fq_act_workspace_bytes(K, Kpad); other arguments, layouts,
+ * ownership and errors as fq_linear_bias.  fq_gemm_select does not apply (one kernel).
+ * ------------------------------------------------------------------------------------------- */
+int fq_linear_fused_a_i8(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx, const int32_t* rep,
+                         int Kpad, const void* Wq, const float* s_w, const float* bias, int N, const float* absmax_in,
+                         void* Y, int y_dtype, int ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * fq_gemm_bf16 — the unquantized baseline the paper compares against (Table 5, "Gemm (FP16)"):
  * Y = X W^T with bf16 operands, fp32 accumulation on the bf16 MFMA, bf16 output.
  * X [M, K], W [N, K] device bf16, dense rows; K a multiple of 8.  Y [M, N] bf16, row stride ldy.

@@ -24,7 +24,7 @@ SYMBOLS = ["fq_last_error_string", "fq_version", "fq_flatten_plan", "fq_flatten_
            "fq_gemm_i4", "fq_linear", "fq_linear_workspace_bytes", "fq_gemm_bf16", "fq_gemm_select",
            "fq_threshold_boxplot", "fq_smooth_scales", "fq_channel_absmax", "fq_bmm_i8", "fq_bmm_i4",
            "fq_flatten_plan_xw", "fq_flatten_weights_split", "fq_flatten_quant_act_peel",
-           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_gemm_i4_e3m2",
+           "fq_gemm_i8_bias", "fq_gemm_i4_bias", "fq_linear_bias", "fq_linear_fused_a_i8", "fq_gemm_i4_e3m2",
            "fq_flatten_quant_act_noalloc", "fq_noalloc_scratch_bytes",
            # include/fq_peak.h: measurement hooks
            "fq_peak_mfma", "fq_peak_copy", "fq_peak_gemm_ticks", "fq_peak_wall_clock_khz"]
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
                       c_int, ctypes.c_longlong, vp]
     for f in (L.fq_gemm_i8_bias, L.fq_gemm_i4_bias, L.fq_gemm_i4_e3m2):
         f.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp, vp, vp, c_int, c_int, vp]
+    L.fq_linear_fused_a_i8.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, vp, c_int, vp, vp, c_int, c_int,
+                                       vp, c_size_t, vp]
     L.fq_linear_bias.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, vp, c_int, c_int, vp, vp,
                                  c_int, c_int, vp, c_size_t, vp]
     L.fq_linear.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp, c_int, vp, vp, c_int, c_int, vp, vp, c_int,
@@ -345,6 +347,22 @@ def fq_linear_bias(X, src_idx, rep, Wq, s_w, bias, bits: int, Y, workspace, absm
                                 Kpad, Wq.data_ptr(), s_w.data_ptr(), _ptr(bias), N, bits, _ptr(absmax_in), Y.data_ptr(),
                                 _dtype_code(Y), Y.stride(0), workspace.data_ptr(),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fq_linear_fused_a_i8(X, src_idx, rep, Wq, s_w, Y, workspace, bias=None, absmax_in=None, stream=None) -> None:
+    """The INT8 layer with flatten + quantize fused into the GEMM's A-operand load: X bf16 [M, K], Wq int8 [N, Kpad]
+    -> Y [M, N]; workspace of fq_act_workspace_bytes(K, Kpad) bytes."""
+    _dev2d(X, "X")
+    _dev2d(Y, "Y")
+    M, K = X.shape
+    Kpad = src_idx.numel()
+    N = Wq.shape[0]
+    if bias is not None and (bias.numel() != N or _dtype_code(bias) != FQ_F32 or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous fp32 tensor of N elements")
+    _check(lib().fq_linear_fused_a_i8(X.data_ptr(), _dtype_code(X), M, K, X.stride(0), src_idx.data_ptr(), rep.data_ptr(),
+                                      Kpad, Wq.data_ptr(), _ptr(s_w), _ptr(bias), N, _ptr(absmax_in), Y.data_ptr(),
+                                      _dtype_code(Y), Y.stride(0), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def fq_gemm_i4(Xq, Wq, s_x, s_w, Y, stream=None) -> None:

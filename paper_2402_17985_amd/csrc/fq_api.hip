@@ -531,6 +531,40 @@ int fq_linear_bias(const void* X, int x_dtype, int M, int K, int ldx, const int3
     return launch_gemm_int(Xq, Wq, M, N, Kpad, bits, s_x, s_w, Y, y_dtype, ldy, st, bias);
 }
 
+int fq_linear_fused_a_i8(const void* X, int x_dtype, int M, int K, int ldx, const int32_t* src_idx, const int32_t* rep,
+                         int Kpad, const void* Wq, const float* s_w, const float* bias, int N, const float* absmax_in,
+                         void* Y, int y_dtype, int ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_matrix("X", X, x_dtype, M, K, ldx);
+    if (rc) return rc;
+    if (x_dtype != FQ_BF16) return fail(FQ_ERR_DTYPE, "the fused A-operand path reads bf16 activations only");
+    rc = check_map(src_idx, Kpad, 8);
+    if (rc) return rc;
+    if (!rep || !workspace) return fail(FQ_ERR_NULL, "rep or workspace is NULL");
+    if (!aligned16(workspace)) return fail(FQ_ERR_ALIGN, "workspace is not 16-byte aligned");
+    if (workspace_bytes < fq_act_workspace_bytes(K, Kpad))
+        return fail(FQ_ERR_WORKSPACE, "workspace of %zu bytes < %zu required", workspace_bytes, fq_act_workspace_bytes(K, Kpad));
+    if (!Wq || !Y) return fail(FQ_ERR_NULL, "Wq or Y is NULL");
+    if (y_dtype != FQ_F32 && y_dtype != FQ_F16 && y_dtype != FQ_BF16 && y_dtype != FQ_I32)
+        return fail(FQ_ERR_DTYPE, "unsupported output dtype %d", y_dtype);
+    if (y_dtype != FQ_I32 && !s_w) return fail(FQ_ERR_NULL, "s_w is NULL");
+    if (N <= 0) return fail(FQ_ERR_SHAPE, "non-positive N = %d", N);
+    if (ldy < N) return fail(FQ_ERR_SHAPE, "ldy = %d < N = %d", ldy, N);
+    if (!aligned16(Wq)) return fail(FQ_ERR_ALIGN, "Wq is not 16-byte aligned");
+    if ((unsigned long long)N * (unsigned long long)Kpad >= (1ull << 32))
+        return fail(FQ_ERR_RANGE, "a quantized operand of 4 GiB or more");
+    rc = check_bias(bias, y_dtype);
+    if (rc) return rc;
+    ActWorkspace ws = carve_act_workspace(workspace, K, Kpad);
+    float* s_x = ws.scalars + 1;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the scale, the per-slot multipliers and the group flags; nothing is quantized here
+    rc = launch_flatten_quant(X, x_dtype, M, K, ldx, src_idx, rep, Kpad, 8, absmax_in ? 1 : 0, absmax_in, nullptr, s_x, ws, st);
+    if (rc) return rc;
+    return launch_gemm_fused_a_i8(X, ldx, K, src_idx, ws.mslot, ws.gflag, Wq, M, N, Kpad, s_x, s_w, Y, y_dtype, ldy, bias, st);
+}
+
 int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy, void* stream)
 {
     clear_error();

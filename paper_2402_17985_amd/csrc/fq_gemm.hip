@@ -50,6 +50,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -1855,6 +1856,191 @@ int gemm_dispatch_f6(const void* A, const void* B, int M, int N, int rowbytes, c
     return FQ_OK;
 }
 #elif FQ_GEMM_MODE == 0
+// =============================================================================================
+// gemm_fused_a_kernel: flatten-quantize fused into the A-operand load (Sec. 6, the paper's future work)
+// =============================================================================================
+// gemm_reg_kernel (128 x 128 tile, 64-byte k-stages, four waves, operands staged through registers) with the
+// loader of A replaced: a thread's 16-byte chunk of a quantized row is 16 flattened slots p0 .. p0 + 15, which it
+// forms itself from X -- two 16-byte loads of bf16 when the group is 16 consecutive channels (gflag), 16 gathered
+// elements X[row, src[p]] otherwise -- times the slots' multipliers, rounded half-to-even and clamped exactly as
+// the separate quantizer does (one fp32 multiply per element), packed and written to the same LDS position.
+// X'q never exists in memory.  Every column tile of the output converts its rows of X again.
+namespace {
+__device__ __forceinline__ int quantize_i8(float x, float m)
+{
+    float r = rintf(x * m);
+    r = fminf(fmaxf(r, -128.0f), 127.0f);
+    return (int)r;
+}
+
+template <int BM, int BN, int BKB, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_fused_a_kernel(const uint16_t* __restrict__ X, int ldx, int K,
+                                                                    const int32_t* __restrict__ src,
+                                                                    const float* __restrict__ mslot,
+                                                                    const uint8_t* __restrict__ gflag,
+                                                                    const uint8_t* __restrict__ B, int M, int N, int rowbytes,
+                                                                    const float* __restrict__ s_x,
+                                                                    const float* __restrict__ s_w, void* __restrict__ Y,
+                                                                    int y_dtype, int ldy, int tiles_m, int tiles_n,
+                                                                    const float* __restrict__ bias)
+{
+    constexpr int MODE = MODE_I8;
+    constexpr int NT = WM * WN * 64;
+    constexpr int CPR = BKB / 16, RPP = NT / CPR;
+    constexpr int A_LOADS = BM / RPP, B_LOADS = BN / RPP;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int KS = BKB / 32;
+    constexpr int STAGE = (BM + BN) * BKB;
+    constexpr int SWZ_SHIFT = (CPR == 8) ? 1 : 2, SWZ_MASK = CPR - 1;
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && RPP % 16 == 0 && (CPR == 4 || CPR == 8), "loader layout");
+    typedef typename Acc<MODE>::type acc_t;
+    const float scale = tile_scale<MODE>(s_x, s_w);
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int lc = tid % CPR, lr = tid / CPR;
+    const uint16_t* gX[A_LOADS];
+    const uint8_t* gB[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) gX[i] = X + (size_t)min(m0 + lr + i * RPP, M - 1) * ldx;
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) gB[i] = B + (size_t)min(n0 + lr + i * RPP, N - 1) * rowbytes + lc * 16;
+    const int wofs = lr * BKB + ((lc ^ ((lr >> SWZ_SHIFT) & SWZ_MASK)) << 4);
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = (frow >> SWZ_SHIFT) & SWZ_MASK;
+    int kofs[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kofs[ks] = ((2 * ks + fhalf) ^ fsw) << 4;
+    const int a_rd = (wm * TM + frow) * BKB;
+    const int b_rd = BM * BKB + (wn * TN + frow) * BKB;
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int nk = (rowbytes + BKB - 1) / BKB;
+    v4i rb[B_LOADS];
+    uint32_t xa[A_LOADS][8];                     // 16 bf16 elements per row, two per register
+    float mv[16];
+    bool ok = false;
+
+    auto load_global = [&](int kt) {
+        const int p0 = kt * BKB + lc * 16;       // first of this thread's 16 slots
+        ok = p0 < rowbytes;
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i)
+            rb[i] = ok ? *reinterpret_cast<const v4i*>(gB[i] + kt * BKB) : v4i{0, 0, 0, 0};
+        if (!ok) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const v4f m4 = *reinterpret_cast<const v4f*>(mslot + p0 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mv[4 * q + e] = m4[e];
+        }
+        if (gflag[p0 >> 4]) {                    // 16 consecutive channels p0 .. p0 + 15
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i) {
+                const v4u lo = *reinterpret_cast<const v4u*>(gX[i] + p0), hi = *reinterpret_cast<const v4u*>(gX[i] + p0 + 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xa[i][e] = lo[e];
+                    xa[i][4 + e] = hi[e];
+                }
+            }
+        } else {
+            int sp[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4i s4 = *reinterpret_cast<const v4i*>(src + p0 + 4 * q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sp[4 * q + e] = s4[e];
+            }
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int c0 = sp[2 * e], c1 = sp[2 * e + 1];
+                    const uint32_t v0 = ((unsigned)c0 < (unsigned)K) ? gX[i][c0] : 0u;
+                    const uint32_t v1 = ((unsigned)c1 < (unsigned)K) ? gX[i][c1] : 0u;
+                    xa[i][e] = v0 | (v1 << 16);
+                }
+        }
+    };
+    auto store_lds = [&](int stage) {
+        uint8_t* s = smem + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            v4i packed = {0, 0, 0, 0};
+            if (ok) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    uint32_t word = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int e = 4 * w + b;
+                        const uint32_t raw = xa[i][e >> 1];
+                        const float x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+                        word |= (uint32_t)(quantize_i8(x, mv[e]) & 0xff) << (8 * b);
+                    }
+                    packed[w] = (int)word;
+                }
+            }
+            *reinterpret_cast<v4i*>(s + wofs + i * RPP * BKB) = packed;
+        }
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) *reinterpret_cast<v4i*>(s + BM * BKB + wofs + i * RPP * BKB) = rb[i];
+    };
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* s = smem + (kt & 1) * STAGE;
+        if (kt + 1 < nk) load_global(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v4i a[FM], b[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const v4i*>(s + a_rd + i * 32 * BKB + kofs[ks]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const v4i*>(s + b_rd + j * 32 * BKB + kofs[ks]);
+            mfma_slice<MODE, FM, FN>(a, b, acc);
+        }
+        if (kt + 1 < nk) store_lds((kt + 1) & 1);
+        __syncthreads();
+    }
+    store_tile<MODE, FM, FN>(acc, m0 + wm * TM, n0 + wn * TN, M, N, scale, Y, y_dtype, ldy, nullptr, bias);
+}
+}  // namespace
+
+int launch_gemm_fused_a_i8(const void* X, int ldx, int K, const int32_t* src, const float* mslot, const uint8_t* gflag,
+                           const void* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w, void* Y,
+                           int y_dtype, int ldy, const float* bias, hipStream_t stream)
+{
+    constexpr int BM = 128, BN = 128, BKB = 64;
+    auto kern = gemm_fused_a_kernel<BM, BN, BKB, 2, 2>;
+    constexpr int smem = 2 * (BM + BN) * BKB;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const long long tiles = (long long)tiles_m * tiles_n;
+    if (tiles > 0x7fffffffLL) return fail(FQ_ERR_RANGE, "too many tiles");
+    kern<<<dim3((unsigned)tiles), dim3(256), smem, stream>>>(static_cast<const uint16_t*>(X), ldx, K, src, mslot, gflag,
+                                                            static_cast<const uint8_t*>(Wq), M, N, Kpad, s_x, s_w, Y,
+                                                            y_dtype, ldy, tiles_m, tiles_n, bias);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FQ_ERR_HIP, "fused GEMM launch failed: %s", hipGetErrorString(e));
+    return FQ_OK;
+}
+
 int gemm_dispatch_i8(const void* A, const void* B, int M, int N, int rowbytes, const float* s_x, const float* s_w,
                      void* Y, int y_dtype, int ldy, Batch bt, hipStream_t stream)
 {

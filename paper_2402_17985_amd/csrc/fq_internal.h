@@ -39,7 +39,8 @@ ActWorkspace carve_act_workspace(void* base, int K, int Kpad);
 // ---- launchers (each validates nothing: the C-ABI layer has already done so) ----
 // mode 0: equal split, dynamic absmax; 1: equal split, static absmax (*absmax_in); 2: weights (rep
 // ignored, every slot a plain copy); 3 / 4: the printed peel split with threshold T, dynamic / static
-// absmax, `rep` then carrying the slot ordinals
+// absmax, `rep` then carrying the slot ordinals.  out == nullptr: only the scale, the per-slot multipliers and
+// the group flags are produced (in ws), nothing is quantized
 int launch_flatten_quant(const void* X, int x_dtype, int M, int K, int ld,
                          const int32_t* src_idx, const int32_t* rep, int Kpad, int bits,
                          int mode, const float* absmax_in, void* out, float* scale_out,
@@ -86,5 +87,10 @@ int launch_bmm_int(const void* Aq, const void* Bq, int batch, int M, int N, int 
 
 int launch_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int ldy,
                      hipStream_t stream);
+// INT8 GEMM whose A operand is X itself (bf16, row stride ldx elements): slot p of a row is quantized from
+// X[row, src[p]] * mslot[p] on the way into LDS (gflag marks the 16-slot groups that are 16 consecutive channels)
+int launch_gemm_fused_a_i8(const void* X, int ldx, int K, const int32_t* src, const float* mslot, const uint8_t* gflag,
+                           const void* Wq, int M, int N, int Kpad, const float* s_x, const float* s_w, void* Y,
+                           int y_dtype, int ldy, const float* bias, hipStream_t stream);
 
 }  // namespace fq

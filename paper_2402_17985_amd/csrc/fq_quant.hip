@@ -734,6 +734,12 @@ int launch_for_dtype(const void* X, int M, int K, int ld, const int32_t* src_idx
     if (mode != 1 && mode != 4) launch_colabsmax<DT>(X, M, K, ld, /*accumulate=*/false, ws.cmax, stream);
     scale_kernel<<<(Kpad + 1023) / 1024, 1024, 0, stream>>>(ws.cmax, K, src_idx, rep, Kpad, qmax, mode, absmax_in, T,
                                                             ws.mslot, scale_out, ws.scalars, ws.gflag);
+    if (!out) {
+        // scales only: the caller quantizes elsewhere (the GEMM that converts its A operand on the way into LDS)
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(FQ_ERR_HIP, "activation scale launch failed: %s", hipGetErrorString(e));
+        return FQ_OK;
+    }
     uint8_t* o8 = static_cast<uint8_t*>(out);
     if (!peel && K >= 16) {
         // row-strip kernel: R rows per workgroup with R * K bytes of LDS plus 2 bytes per appended slot

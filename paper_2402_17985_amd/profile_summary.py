@@ -4,6 +4,7 @@
     python -m paper_2402_17985_amd.profile_summary pmc     <dir> <out.txt>  "<command that made dir>"
     python -m paper_2402_17985_amd.profile_summary traffic <fetch dir> <write dir> <out.txt> <out.json> "<commands>"
     python -m paper_2402_17985_amd.profile_summary table   <out.txt> <bench line>.json [...] [--static <bench line>.json ...]
+    python -m paper_2402_17985_amd.profile_summary fused   <out.txt> <bench line>.json   (a `bench.py --fused` run)
 
 stats:   per-kernel call count, total and average duration from a `--kernel-trace --stats` run.
 pmc:     per-kernel mean of every counter of a `--pmc` run.
@@ -159,6 +160,21 @@ def cmd_table(out, files, static_files):
     print("\n".join(L))
 
 
+def cmd_fused(out, fn):
+    d = json.loads(open(fn).read().strip().split("\n")[-1])
+    L = ["fq_linear_fused_a_i8 (flatten + quantize fused into the GEMM's A-operand load) against quantize-then-GEMM, INT8, bf16 in / out,",
+         "one MI355X, HIP-event averages.  command:  python3 bench.py --no-cpu --no-peak --no-bmm --no-alt --fused --steps 40 --warmup 20",
+         "default = fq_linear as dispatched (flatten-quantize kernel, then the large-problem GEMM); same tile = fq_linear with the GEMM forced",
+         "to the 128 x 128 register-staged kernel whose structure the fused kernel shares; fused = fq_linear_fused_a_i8.", "",
+         f"{'layer':14s} {'M':>6s} {'K':>6s} {'N':>6s} {'Kpad':>6s} {'scale':>8s} {'default us':>11s} {'same tile us':>13s} {'fused us':>9s} {'fused/default':>13s} {'fused/same tile':>15s} {'identical':>9s}"]
+    for r in d["fused_a_operand"]:
+        L.append(f"{r['layer']:14s} {r['M']:6d} {r['K']:6d} {r['N']:6d} {r['Kpad']:6d} {r['scale']:>8s} {r['ms_quantize_then_gemm'] * 1e3:11.1f} "
+                 f"{r['ms_quantize_then_gemm_same_tile'] * 1e3:13.1f} {r['ms_fused'] * 1e3:9.1f} {r['ms_fused'] / r['ms_quantize_then_gemm']:13.2f} "
+                 f"{r['ms_fused'] / r['ms_quantize_then_gemm_same_tile']:15.2f} {str(r['outputs_identical']):>9s}")
+    open(out, "w").write("\n".join(L) + "\n")
+    print("\n".join(L))
+
+
 if __name__ == "__main__":
     a = sys.argv[1:]
     if len(a) == 4 and a[0] == "stats":
@@ -167,6 +183,8 @@ if __name__ == "__main__":
         cmd_pmc(a[1], a[2], a[3])
     elif len(a) == 6 and a[0] == "traffic":
         cmd_traffic(a[1], a[2], a[3], a[4], a[5])
+    elif len(a) == 3 and a[0] == "fused":
+        cmd_fused(a[1], a[2])
     elif len(a) >= 3 and a[0] == "table":
         rest = a[2:]
         k = rest.index("--static") if "--static" in rest else len(rest)
