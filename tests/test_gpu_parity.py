@@ -767,6 +767,31 @@ def test_gemm_four_wave_kernel_several_rounds_bf16(bits, Kpad):
     assert np.array_equal(bits16(Y), want)
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_four_wave_kernel_random_shapes(bits):
+    """Variant 12 on 24 seeded random shapes (1..700 rows and columns, 1..12 k-stages, every tile raggedness): raw
+    accumulators against the oracle, and the bf16 bits of the same product through the bf16-only instantiation."""
+    rng = np.random.default_rng(1500 + bits)
+    stage = 128 if bits == 8 else 256
+    fq.fq_gemm_select(12)
+    try:
+        for case in range(24):
+            M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+            Kpad = stage * int(rng.integers(1, 13))
+            Xq, Wq = _rand_q(rng, M, Kpad, bits), _rand_q(rng, N, Kpad, bits)
+            ref = O.gemm_i32(Xq, Wq)
+            assert np.array_equal(_gemm_acc(Xq, Wq, bits), ref), (case, M, N, Kpad)
+            Npad = (N + 7) // 8 * 8
+            Y = torch.full((M, Npad), 5.0, dtype=torch.bfloat16, device=DEV)
+            s_x, s_w = np.float32(rng.uniform(1e-3, 1e-1)), np.float32(rng.uniform(1e-4, 1e-2))
+            (fq.fq_gemm_i8 if bits == 8 else fq.fq_gemm_i4)(_to_dev_2d(Xq, bits), _to_dev_2d(Wq, bits), scalar(s_x), scalar(s_w), Y[:, :N])
+            torch.cuda.synchronize()
+            assert np.array_equal(bits16(Y[:, :N]), O.dequant_out(ref, s_x, s_w, "bf16")), (case, M, N, Kpad)
+            assert (Y[:, N:].float() == 5.0).all()
+    finally:
+        fq.fq_gemm_select(-1)
+
+
 def _to_dev_2d(q, bits):
     return torch.from_numpy(q if bits == 8 else O.pack_i4(q)).to(DEV)
 
