@@ -228,8 +228,11 @@ int fq_flatten_quant_act_peel(const void* X, int x_dtype, int M, int K, int ldx,
  * dequantize epilogue (Sec. 5.1; the inverse of Eq. 1 applied to the product).
  *
  *   acc[i,n] = sum_{p < Kpad} Xq[i,p] * Wq[n,p]                      (exact, int32)
- *   Y[i,n]   = round_to_y_dtype( fl32(acc[i,n]) * fl32(*s_x * *s_w) )   for F32 / F16 / BF16
+ *   Y[i,n]   = round_to_y_dtype( fl32( fl32(acc[i,n]) * fl32(*s_x * *s_w) ) )   for F32 / F16 / BF16
  *   Y[i,n]   = acc[i,n]                                                for FQ_I32 (scales may be NULL)
+ * Two roundings for 2-byte outputs: the product is rounded to fp32 first and that value is rounded (half to
+ * even; halves overflow to infinity and go subnormal as IEEE prescribes) to the output type.  Every stored bit
+ * is defined by this and is what the tests compare.
  *
  * fq_gemm_i4 takes both operands packed two per byte ([M, Kpad/2], [N, Kpad/2]); they stay
  * packed in HBM and LDS and are widened to int8 in registers (gfx950 has no 4-bit MFMA).
