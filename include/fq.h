@@ -373,8 +373,9 @@ int fq_gemm_bf16(const void* X, const void* W, int M, int N, int K, void* Y, int
  *       reads and copies dealt out per MFMA slot.
  *   12: as 11 with all of LDS as stage buffers (A three deep, B two deep) so that the global->LDS copies are
  *       spread over the whole stage, one copy instruction of one wave per MFMA slot; also for packed INT4, whose
- *       nibble widening is dealt out over the MFMA slots as well.  The choice for large problems with such rows
- *       and a bf16 output without bias; other outputs keep 7 (INT8, bf16) or 10 (INT4).
+ *       nibble widening is dealt out over the MFMA slots as well.  The choice for problems of 80 (INT8, bf16) or
+ *       176 (INT4) tiles and more with such rows and a bf16 output without bias; other outputs keep 7 (INT8,
+ *       bf16) or 10 (INT4).
  *   6:  128x128 tile, 4 waves, direct global->LDS copies (small problems, narrow outputs).
  *   2:  128x128 tile, 64-byte k-stages, 4 waves, operands staged through registers.
  * fq_gemm_i4_e3m2 has a single kernel and ignores the hook.

@@ -1786,17 +1786,28 @@ int dispatch(const void* A, const void* B, int M, int N, int rowbytes, const flo
     int v = forced_gemm_variant();
     if (v < 0) {
         const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256) * bt.count;
-        // narrow outputs (N <= 128, the P V product of attention) and small problems use the 128x128 tile
-        // long phases (10) where the operand registers allow it: INT8 and bf16 would hold four unpacked
-        // k-slices per phase and spill, so they keep two k-slices per phase (7), as do reductions of
-        // only a few k-stages (attention's Q K^T)
-        v = (big_tiles >= 192 && N > 128) ? ((MODE == MODE_I4 && rowbytes >= 512) ? 10 : 7) : 6;
-        // rows of whole 128-byte stages, bf16 output and no bias (the instantiation with that epilogue only): the
-        // four-wave kernel with the deep staging (INT8 and bf16: +14 % over the ping-pong kernel at full clock,
-        // +3-5 % at the clock the power limit leaves on live operands; packed nibbles: +1-5 % on live operands)
-        if ((v == 7 || v == 10) && MODE != MODE_F6 && rowbytes % 128 == 0 && bt.count == 1 && y_dtype == FQ_BF16 &&
-            !bt.bias)
-            v = 12;
+        // The four-wave kernel with the deep staging (12) needs rows of whole 128-byte stages and exists with the
+        // plain bf16 epilogue as its spill-free instantiation: taken for that output, without bias, unbatched.  On
+        // large problems it gains +14 % over the ping-pong kernel at full clock for INT8 and bf16 (+3-5 % at the
+        // clock the power limit leaves on live operands) and +1-5 % for packed nibbles.  Thresholds measured at
+        // N = 4096 in steps of one tile row: INT8 takes it from 80 tiles on (its partly filled rounds run as
+        // half-height tiles on twice as many CUs: 20 % faster than the 128 x 128 tile at 144-176 tiles), nibbles from
+        // 176; otherwise the ping-pong kernel (long phases, 10, where the operand registers allow it: packed nibbles
+        // with at least four k-stages; INT8 and bf16 would hold four unpacked k-slices per phase and spill, so they
+        // keep two per phase, 7) from 144 / 112 tiles on; narrow outputs (N <= 128, the P V product of attention) and
+        // small problems use the 128 x 128 tile (6).
+        const bool deep_ok = MODE != MODE_F6 && rowbytes % 128 == 0 && bt.count == 1 && y_dtype == FQ_BF16 && !bt.bias;
+        v = 6;
+        if (N > 128) {
+            if (MODE == MODE_I4 && rowbytes >= 512) {
+                if (big_tiles >= 112) v = (big_tiles >= 176 && deep_ok) ? 12 : 10;
+            } else if (MODE == MODE_I4) {
+                if (big_tiles >= 192) v = 7;
+            } else {
+                if (big_tiles >= 80 && deep_ok) v = 12;
+                else if (big_tiles >= 144) v = 7;
+            }
+        }
     }
     switch (v) {
     case 2: return launch_reg<MODE, 128, 128, 64, 2, 2>(A, B, M, N, rowbytes, s_x, s_w, Y, y_dtype, ldy, bt, stream);
